@@ -1,0 +1,189 @@
+/*
+ * maskkv.h - C ABI of the MaskKV eviction hot path for AMD MI355X (gfx950).
+ *
+ * The library implements, for one transformer layer at a time, the data-parallel steps
+ * of MaskKV (arXiv 2510.09309, Section 3.3 "The MaskKV Framework"):
+ *
+ *   maskkv_score    Stage 1 "Mask-Voting": A = softmax_row(Q_mask K_full^T / sqrt(d_k)),
+ *                   I_j = sum_i A_ij for the prompt tokens j.
+ *   maskkv_select   S_keep = argtopk(I, k_{l,h}) per (layer, head) with ragged budgets
+ *                   (last equation of Stage 2), after an optional smoothing window.
+ *   maskkv_compact  eviction: the cache keeps only the selected prompt K/V rows
+ *                   (appendix "Prompt-state Exclusion": only prompt K/V are cached).
+ *   maskkv_attend   bidirectional attention of the response span over
+ *                   [kept prompt KV ; response KV] (layer forward equation, Section 3.1;
+ *                   appendix proof: AttnOut_m = sum_j alpha_mj V_j).
+ *   maskkv_attend_full   the same attention over the un-evicted sequence (the cost the
+ *                   eviction removes; used for the speed-up figure).
+ *   maskkv_head_budgets  Stage 2, head level: prompt preference P_h and
+ *                   k_{l,h} = floor(alpha k_l + (1-alpha) N_h k_l P_h / sum_j P_j).
+ *
+ * Conventions
+ *  - Every pointer marked DEVICE must be device memory reachable from the current HIP
+ *    device; pointers marked HOST are ordinary host memory read during the call only.
+ *  - The library never allocates, frees or synchronises.  All work is enqueued on the
+ *    given stream (a hipStream_t passed as void*; NULL is the default stream).  The
+ *    caller owns every buffer, including the workspace, and must keep it alive until the
+ *    stream has drained.  Inputs are never modified; outputs are fully overwritten in
+ *    their valid region.
+ *  - Every function returns a maskkv_status.  On any status other than MASKKV_OK nothing
+ *    has been enqueued.  maskkv_last_error() gives a per-thread detail string.
+ *  - Sequences: batch item b has P_b prompt tokens followed by n_resp response-span
+ *    tokens (N_b = P_b + n_resp keys).  Heads are independent (MHA; one KV head per
+ *    query head).
+ */
+#ifndef MASKKV_H
+#define MASKKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MASKKV_VERSION 1
+#define MASKKV_MAX_BATCH 64 /* per call; split larger batches */
+
+typedef enum maskkv_status {
+  MASKKV_OK = 0,
+  MASKKV_EINVAL = 1,     /* null pointer, negative size, bad window, bad stride, ... */
+  MASKKV_ESHAPE = 2,     /* unsupported head_dim (64 and 128 are supported) or batch too large */
+  MASKKV_EDTYPE = 3,     /* dtype is neither MASKKV_F32 nor MASKKV_BF16 */
+  MASKKV_EWORKSPACE = 4, /* workspace missing or smaller than maskkv_*_workspace_bytes */
+  MASKKV_EHIP = 5,       /* a HIP launch failed; detail string carries hipGetErrorString */
+  MASKKV_ECAPACITY = 6   /* (host-checkable) output capacity too small */
+} maskkv_status;
+
+typedef enum maskkv_dtype { MASKKV_F32 = 0, MASKKV_BF16 = 1 } maskkv_dtype;
+
+typedef enum maskkv_pool_mode { MASKKV_POOL_MEAN = 0, MASKKV_POOL_MAX = 1 } maskkv_pool_mode;
+
+/*
+ * A 4-D view [B, H, T, d] of Q, K, V or O in DEVICE memory.  Element (b, h, t, e) lives at
+ *   ptr + ((b*stride_b + h*stride_h + (seq_start[b] + t)*stride_t + e) * sizeof(element)),
+ * strides in elements, the head_dim axis contiguous.  Rows must be 16-byte aligned
+ * (ptr and all strides multiples of 16 bytes).  [B,H,T,d], [B,T,H,d] and packed
+ * variable-length [T_total,H,d] (stride_b = 0 with seq_start) are all expressible.
+ */
+typedef struct maskkv_tensor {
+  void* ptr;             /* DEVICE */
+  int64_t stride_b;
+  int64_t stride_h;
+  int64_t stride_t;
+  const int32_t* seq_start; /* HOST [B] token offset of each sequence on the T axis, or NULL for 0 */
+} maskkv_tensor;
+
+/* Problem description shared by all calls. */
+typedef struct maskkv_desc {
+  int32_t B;        /* sequences in the batch, 1..MASKKV_MAX_BATCH */
+  int32_t H;        /* attention heads */
+  int32_t d;        /* head_dim: 64 or 128 */
+  int32_t dtype;    /* maskkv_dtype of Q, K, V, the cache and O */
+  int32_t n_resp;   /* response-span length n_m: response keys per sequence; queries in attend */
+  int32_t n_query;  /* mask queries that vote in maskkv_score (normally n_resp; a sub-span is allowed) */
+  int32_t P_max;    /* longest prompt in the batch */
+  int32_t reserved; /* must be 0 */
+  const int32_t* prompt_len; /* HOST [B] prompt lengths P_b in 0..P_max, or NULL: every P_b = P_max */
+} maskkv_desc;
+
+/* Library version (MASKKV_VERSION of the build). */
+int maskkv_version(void);
+/* Static string for a status code. */
+const char* maskkv_strerror(int status);
+/* Detail of the calling thread's most recent failure ("" if none). */
+const char* maskkv_last_error(void);
+
+/*
+ * Workspace (DEVICE bytes) needed by maskkv_score for this description.  The workspace
+ * holds per-key-chunk softmax row statistics between the two passes; contents are
+ * scratch.  256-byte alignment is required.
+ */
+int maskkv_score_workspace_bytes(const maskkv_desc* desc, size_t* bytes);
+
+/*
+ * Stage 1, Mask-Voting.  For every (b, h):
+ *   A = softmax over all N_b keys of (Q_mask[b,h] K_full[b,h]^T * scale)   (no mask)
+ *   scores[(b*H + h)*score_stride + j] = sum_{i < n_query} A[i, j],  j in [0, P_b)
+ *   prompt_mass[b*H + h] = sum_{j < P_b} scores[..j]   (the mask-to-prompt attention sum
+ *                          S_{m->p} of the prompt-preference metric), if not NULL.
+ * Q_mask: view [B, H, n_query, d].  K_full: view [B, H, N_b, d], prompt rows then
+ * response rows.  scale <= 0 selects 1/sqrt(d).  scores: DEVICE float, score_stride >=
+ * P_max; entries j >= P_b are left untouched.  Accumulation is fp32 throughout.
+ */
+int maskkv_score(const maskkv_desc* desc, const maskkv_tensor* Q_mask, const maskkv_tensor* K_full,
+                 float scale, float* scores, int64_t score_stride, float* prompt_mass,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* Workspace (DEVICE bytes) needed by maskkv_select (may be 0). 256-byte alignment. */
+int maskkv_select_workspace_bytes(const maskkv_desc* desc, size_t* bytes);
+
+/*
+ * Smoothing + per-head top-k.  For every (b, h), with k = min(max(budgets[b*H+h], 0), P_b):
+ *   pooled_j = mean (MASKKV_POOL_MEAN) or max (MASKKV_POOL_MAX) of scores over the window
+ *              [max(0, j-r), min(P_b-1, j+r)], r = (pool_window-1)/2; the mean is evaluated
+ *              in fp32 by adding the in-range terms from the lowest index upwards and
+ *              dividing by their count.  pool_window must be odd, 1 (= no pooling) .. 63.
+ *   keep     = the k positions with the largest pooled score, ties to the lower position,
+ *              written in ascending order to idx[cu_budget[b*H+h] .. cu_budget[b*H+h+1]).
+ *   cu_budget = exclusive prefix sum of the clamped budgets, B*H+1 entries.
+ * budgets: DEVICE int32 [B*H] (device-resident so that maskkv_head_budgets can feed it
+ * without a host round trip).  idx: DEVICE int32 [capacity]; cu_budget: DEVICE int32
+ * [B*H+1].  If the clamped budgets sum to more than capacity, rows beyond capacity are not
+ * written (and cu_budget still holds the unclipped prefix sums): size capacity as
+ * sum of budgets, or B*H*k_l for budgets from maskkv_head_budgets.
+ */
+int maskkv_select(const maskkv_desc* desc, const float* scores, int64_t score_stride,
+                  int pool_window, int pool_mode, const int32_t* budgets,
+                  int32_t* idx, int32_t* cu_budget, int64_t capacity,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Eviction as a gather.  Row r of the packed caches, r in [cu_budget[bh], cu_budget[bh+1]),
+ * receives prompt row idx[r] of head bh:  Kc[r, :] = K[b, h, idx[r], :], same for V.
+ * Kc, Vc: DEVICE [capacity, d] in desc->dtype, rows contiguous.  Rows >= min(capacity,
+ * cu_budget[B*H]) are left untouched.  K, V: views whose first P_b rows are the prompt.
+ */
+int maskkv_compact(const maskkv_desc* desc, const maskkv_tensor* K, const maskkv_tensor* V,
+                   const int32_t* idx, const int32_t* cu_budget, int64_t capacity,
+                   void* Kc, void* Vc, void* stream);
+
+/* Workspace (DEVICE bytes) for maskkv_attend / maskkv_attend_full (key-split partial results). */
+int maskkv_attend_workspace_bytes(const maskkv_desc* desc, int full, size_t* bytes);
+
+/*
+ * Attention over the evicted cache.  For every (b, h) and response query i < n_resp:
+ *   O[b,h,i,:] = sum_j softmax_j(Q_resp[b,h,i,:] . k_j * scale) v_j
+ * with j over the cache rows [cu_budget[bh], cu_budget[bh+1]) of Kc/Vc (DEVICE [capacity, d];
+ * row numbers are clipped to capacity) followed by the n_resp rows of K_resp/V_resp (views
+ * [B, H, n_resp, d]).  No mask.  lse (DEVICE float
+ * [B*H*n_resp], optional) receives the natural-log softmax normaliser of every row.
+ * Inputs in desc->dtype, fp32 accumulation; probabilities are rounded to desc->dtype only
+ * as the operand of the P.V product.  O: view [B, H, n_resp, d], written in desc->dtype.
+ */
+int maskkv_attend(const maskkv_desc* desc, const maskkv_tensor* Q_resp,
+                  const void* Kc, const void* Vc, const int32_t* cu_budget, int64_t capacity,
+                  const maskkv_tensor* K_resp, const maskkv_tensor* V_resp, float scale,
+                  const maskkv_tensor* O, float* lse,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* The same attention over all N_b = P_b + n_resp rows of K_full/V_full (nothing evicted). */
+int maskkv_attend_full(const maskkv_desc* desc, const maskkv_tensor* Q_resp,
+                       const maskkv_tensor* K_full, const maskkv_tensor* V_full, float scale,
+                       const maskkv_tensor* O, float* lse,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Stage 2, head level, on the device.  For every b:
+ *   P_h = prompt_mass[b*H+h] / n_query  (mask-to-prompt share of the mask rows' attention)
+ *   budgets[b*H+h] = floor(alpha*k_l + (1-alpha) * H * k_l * P_h / sum_h' P_h')
+ * prompt_mass: DEVICE float [B*H] as written by maskkv_score; budgets: DEVICE int32 [B*H].
+ * k_l is the layer's per-head average budget; 0 <= alpha <= 1.
+ */
+int maskkv_head_budgets(const maskkv_desc* desc, const float* prompt_mass, int32_t k_l, float alpha,
+                        int32_t* budgets, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MASKKV_H */

@@ -1,0 +1,391 @@
+// Bidirectional attention of the response span over [kept prompt KV ; response KV]
+// (MaskKV Section 3.1 layer forward equation; appendix: AttnOut_m = sum_j alpha_mj V_j), and the
+// same attention over the un-evicted sequence.
+//
+// Flash-style single pass with an online softmax.  One workgroup = 4 waves = 128 queries of one (b, h);
+// each wave owns 32 queries.  The logits are formed transposed (keys on the MFMA row axis, queries on
+// the column axis), so a lane owns one query: its running max / sum stay in the lane and the
+// probabilities it holds are already laid out as the B operand of O^T = V^T P^T.  V tiles are written
+// to LDS transposed so that the A operand of that product is read with 8/16-byte LDS loads.
+// The key axis is the concatenation of two segments (packed cache rows, then a strided view); long key
+// axes are split across workgroups and merged by a second small kernel.
+#include "kernels.hpp"
+
+namespace maskkv {
+
+namespace {
+
+constexpr int kAttThreads = 256;
+constexpr int kAttWaves = 4;
+constexpr int kQPerBlock = kAttWaves * 32;
+
+template <typename T, int D>
+struct AttCfg {
+  static constexpr int kRowB = D * (int)sizeof(T);
+  static constexpr int kRowP = kRowB + 16;
+  static constexpr int kSteps = kRowB / 32;
+  static constexpr int kTK = (kRowB <= 256) ? 64 : 32;
+  static constexpr int kNKB = kTK / 32;
+  static constexpr int kPiecesPerRow = kRowB / 16;
+  static constexpr int kPieces = kTK * kRowB / 16 / kAttThreads;
+  static constexpr int kSV = kTK + 4;  // elements per transposed-V row (padding keeps LDS reads conflict-free)
+  static constexpr int kDB = D / 32;
+};
+
+struct AttendParams {
+  View Q, K2, V2, O;
+  Lens lens;
+  const char* Kc;
+  const char* Vc;
+  const int32_t* cu;
+  int64_t capacity;
+  int H, n_resp, full, n_splits;
+  float c;  // scale * log2(e)
+  float* lse;
+  float* part_o;     // [BH][n_splits][n_resp][D]
+  float2* part_ml;   // [BH][n_splits][n_resp]
+};
+
+struct KeySpace {
+  const char* a_k;  // packed segment base (row 0 of this head), rows contiguous
+  const char* a_v;
+  int len_a;
+  int len_b;
+};
+
+template <typename T, int D>
+__device__ __forceinline__ void load_kv(const AttendParams& prm, const KeySpace& ks, int b, int h, int key0, int klast,
+                                        u32x4 (&kr)[AttCfg<T, D>::kPieces], u32x4 (&vr)[AttCfg<T, D>::kPieces]) {
+  using C = AttCfg<T, D>;
+#pragma unroll
+  for (int i = 0; i < C::kPieces; ++i) {
+    const int p = threadIdx.x + i * kAttThreads;
+    {
+      const int row = p / C::kPiecesPerRow, col = p % C::kPiecesPerRow;
+      const int j = min(key0 + row, klast);
+      const char* src = j < ks.len_a ? ks.a_k + (int64_t)j * C::kRowB : prm.K2.row(b, h, j - ks.len_a);
+      kr[i] = *reinterpret_cast<const u32x4*>(src + col * 16);
+    }
+    {
+      int row, col;
+      if (sizeof(T) == 2) {  // item = (key pair, 16-byte slice); pieces 2i and 2i+1 are the pair's two rows
+        const int item = threadIdx.x + (i / 2) * kAttThreads;
+        row = 2 * (item / C::kPiecesPerRow) + (i & 1);
+        col = item % C::kPiecesPerRow;
+      } else {
+        row = p / C::kPiecesPerRow;
+        col = p % C::kPiecesPerRow;
+      }
+      const int j = min(key0 + row, klast);
+      const char* src = j < ks.len_a ? ks.a_v + (int64_t)j * C::kRowB : prm.V2.row(b, h, j - ks.len_a);
+      vr[i] = *reinterpret_cast<const u32x4*>(src + col * 16);
+    }
+  }
+}
+
+template <typename T, int D>
+__device__ __forceinline__ void store_kv(char* kt, char* vt, const u32x4 (&kr)[AttCfg<T, D>::kPieces],
+                                         const u32x4 (&vr)[AttCfg<T, D>::kPieces]) {
+  using C = AttCfg<T, D>;
+#pragma unroll
+  for (int i = 0; i < C::kPieces; ++i) {
+    const int p = threadIdx.x + i * kAttThreads;
+    const int row = p / C::kPiecesPerRow, col = p % C::kPiecesPerRow;
+    *reinterpret_cast<u32x4*>(kt + row * C::kRowP + col * 16) = kr[i];
+  }
+  uint32_t* vt32 = reinterpret_cast<uint32_t*>(vt);
+  if (sizeof(T) == 2) {
+    // vt[e][key] as bf16: a 32-bit word holds keys (2*pair, 2*pair+1) of one head-dim element
+#pragma unroll
+    for (int i = 0; i < C::kPieces / 2; ++i) {
+      const int item = threadIdx.x + i * kAttThreads;
+      const int pair = item / C::kPiecesPerRow, col = item % C::kPiecesPerRow;
+      const u32x4 a = vr[2 * i], bq = vr[2 * i + 1];
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const uint32_t lo = (a[w] & 0xFFFFu) | (bq[w] << 16);
+        const uint32_t hi = (a[w] >> 16) | (bq[w] & 0xFFFF0000u);
+        vt32[(col * 8 + 2 * w) * (C::kSV / 2) + pair] = lo;
+        vt32[(col * 8 + 2 * w + 1) * (C::kSV / 2) + pair] = hi;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < C::kPieces; ++i) {
+      const int p = threadIdx.x + i * kAttThreads;
+      const int row = p / C::kPiecesPerRow, col = p % C::kPiecesPerRow;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) vt32[(col * 4 + w) * C::kSV + row] = vr[i][w];
+    }
+  }
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(kAttThreads) void attend_kernel(const AttendParams prm) {
+  using C = AttCfg<T, D>;
+  __shared__ __attribute__((aligned(16))) char kt[C::kTK * C::kRowP];
+  __shared__ __attribute__((aligned(16))) char vt[D * C::kSV * sizeof(T)];
+
+  const int bh = blockIdx.z;
+  const int split = blockIdx.y;
+  const int b = bh / prm.H;
+  const int h = bh % prm.H;
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int r = lane & 31;
+  const int g = lane >> 5;
+
+  KeySpace ks;
+  if (prm.full) {
+    ks.a_k = ks.a_v = nullptr;
+    ks.len_a = 0;
+    ks.len_b = prm.lens.P[b] + prm.n_resp;
+  } else {
+    const int64_t c0 = min((int64_t)prm.cu[bh], prm.capacity);
+    const int64_t c1 = min((int64_t)prm.cu[bh + 1], prm.capacity);
+    ks.a_k = prm.Kc + c0 * C::kRowB;
+    ks.a_v = prm.Vc + c0 * C::kRowB;
+    ks.len_a = (int)(c1 - c0);
+    ks.len_b = prm.n_resp;
+  }
+  const int Lk = ks.len_a + ks.len_b;
+  const int Ls = ((Lk + prm.n_splits - 1) / prm.n_splits + C::kTK - 1) / C::kTK * C::kTK;
+  const int j0 = split * Ls;
+  const int j1 = min(Lk, j0 + Ls);
+  const int ntiles = j1 > j0 ? (j1 - j0 + C::kTK - 1) / C::kTK : 0;
+
+  const int q = blockIdx.x * kQPerBlock + wave * 32 + r;
+  u32x4 qf[C::kSteps];
+#pragma unroll
+  for (int s = 0; s < C::kSteps; ++s) {
+    if (q < prm.n_resp)
+      qf[s] = *reinterpret_cast<const u32x4*>(prm.Q.row(b, h, q) + s * 32 + g * 16);
+    else
+      qf[s] = u32x4{0u, 0u, 0u, 0u};
+  }
+
+  f32x16 o[C::kDB];
+#pragma unroll
+  for (int db = 0; db < C::kDB; ++db) o[db] = f32x16{};
+  float m = kNegBig, l = 0.f;
+  const float c = prm.c;
+
+  u32x4 kr[C::kPieces], vr[C::kPieces];
+  if (ntiles > 0) load_kv<T, D>(prm, ks, b, h, j0, j1 - 1, kr, vr);
+
+  for (int t = 0; t < ntiles; ++t) {
+    const int key0 = j0 + t * C::kTK;
+    __syncthreads();  // the previous tile's readers are done
+    store_kv<T, D>(kt, vt, kr, vr);
+    __syncthreads();
+    if (t + 1 < ntiles) load_kv<T, D>(prm, ks, b, h, key0 + C::kTK, j1 - 1, kr, vr);
+
+    // S^T = K Q^T for this tile
+    f32x16 s[C::kNKB];
+#pragma unroll
+    for (int kb = 0; kb < C::kNKB; ++kb) {
+      s[kb] = f32x16{};
+#pragma unroll
+      for (int st = 0; st < C::kSteps; ++st) {
+        const u32x4 kf = *reinterpret_cast<const u32x4*>(kt + (kb * 32 + r) * C::kRowP + st * 32 + g * 16);
+        mfma_step<T>(kf, qf[st], s[kb]);
+      }
+      const int nvalid = j1 - (key0 + kb * 32);
+      if (nvalid < 32) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (8 * (i / 4) + 4 * g + (i % 4) >= nvalid) s[kb][i] = -INFINITY;
+      }
+    }
+    // online softmax; lanes l and l^32 hold the same query
+    float bm = s[0][0];
+#pragma unroll
+    for (int kb = 0; kb < C::kNKB; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) bm = fmaxf(bm, s[kb][i]);
+    bm = fmaxf(bm, xor32(bm));
+    const float m_new = fmaxf(m, bm * c);
+    const float alpha = fast_exp2(m - m_new);
+    float psum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < C::kNKB; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float p = fast_exp2(fmaf(s[kb][i], c, -m_new));
+        s[kb][i] = p;
+        psum += p;
+      }
+    l = l * alpha + psum;
+    m = m_new;
+#pragma unroll
+    for (int db = 0; db < C::kDB; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+
+    // O^T += V^T P^T
+    if (sizeof(T) == 2) {
+#pragma unroll
+      for (int kb = 0; kb < C::kNKB; ++kb)
+#pragma unroll
+        for (int tp = 0; tp < 2; ++tp) {
+          u32x4 pf;
+#pragma unroll
+          for (int w = 0; w < 4; ++w)
+            pf[w] = f32_to_bf16_rne(s[kb][8 * tp + 2 * w]) | (f32_to_bf16_rne(s[kb][8 * tp + 2 * w + 1]) << 16);
+#pragma unroll
+          for (int db = 0; db < C::kDB; ++db) {
+            const char* rowp = vt + ((db * 32 + r) * C::kSV + kb * 32 + 16 * tp + 4 * g) * 2;
+            const u32x2 lo = *reinterpret_cast<const u32x2*>(rowp);
+            const u32x2 hi = *reinterpret_cast<const u32x2*>(rowp + 16);
+            const u32x4 vf = {lo[0], lo[1], hi[0], hi[1]};
+            mfma_step<T>(vf, pf, o[db]);
+          }
+        }
+    } else {
+#pragma unroll
+      for (int kb = 0; kb < C::kNKB; ++kb)
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+          u32x4 pf;
+#pragma unroll
+          for (int w = 0; w < 4; ++w) pf[w] = __builtin_bit_cast(uint32_t, s[kb][4 * qd + w]);
+#pragma unroll
+          for (int db = 0; db < C::kDB; ++db) {
+            const u32x4 vf =
+                *reinterpret_cast<const u32x4*>(vt + ((db * 32 + r) * C::kSV + kb * 32 + 8 * qd + 4 * g) * 4);
+            mfma_step<T>(vf, pf, o[db]);
+          }
+        }
+    }
+  }
+
+  const float l_tot = l + xor32(l);
+  if (q >= prm.n_resp) return;
+  if (prm.n_splits == 1) {
+    const float inv = 1.f / l_tot;
+    char* orow = prm.O.row(b, h, q);
+#pragma unroll
+    for (int db = 0; db < C::kDB; ++db)
+#pragma unroll
+      for (int qd = 0; qd < 4; ++qd) {
+        const int e = db * 32 + 8 * qd + 4 * g;
+        const float v0 = o[db][4 * qd] * inv, v1 = o[db][4 * qd + 1] * inv;
+        const float v2 = o[db][4 * qd + 2] * inv, v3 = o[db][4 * qd + 3] * inv;
+        if (sizeof(T) == 2) {
+          u32x2 w;
+          w[0] = f32_to_bf16_rne(v0) | (f32_to_bf16_rne(v1) << 16);
+          w[1] = f32_to_bf16_rne(v2) | (f32_to_bf16_rne(v3) << 16);
+          *reinterpret_cast<u32x2*>(orow + e * 2) = w;
+        } else {
+          *reinterpret_cast<float4*>(orow + e * 4) = make_float4(v0, v1, v2, v3);
+        }
+      }
+    if (prm.lse && g == 0) prm.lse[(int64_t)bh * prm.n_resp + q] = (m + __log2f(l_tot)) * kLn2;
+  } else {
+    const int64_t slot = ((int64_t)bh * prm.n_splits + split) * prm.n_resp + q;
+    float* po = prm.part_o + slot * D;
+#pragma unroll
+    for (int db = 0; db < C::kDB; ++db)
+#pragma unroll
+      for (int qd = 0; qd < 4; ++qd) {
+        const int e = db * 32 + 8 * qd + 4 * g;
+        *reinterpret_cast<float4*>(po + e) =
+            make_float4(o[db][4 * qd], o[db][4 * qd + 1], o[db][4 * qd + 2], o[db][4 * qd + 3]);
+      }
+    if (g == 0) prm.part_ml[slot] = make_float2(m, l_tot);
+  }
+}
+
+// Merge the key splits of one query row: O = sum_s w_s O_s / sum_s w_s l_s, w_s = 2^(m_s - max m).
+template <typename T, int D>
+__global__ __launch_bounds__(D) void attend_merge_kernel(const AttendParams prm) {
+  const int q = blockIdx.x;
+  const int bh = blockIdx.y;
+  const int b = bh / prm.H, h = bh % prm.H;
+  const int e = threadIdx.x;
+  float M = kNegBig;
+  for (int s = 0; s < prm.n_splits; ++s)
+    M = fmaxf(M, prm.part_ml[((int64_t)bh * prm.n_splits + s) * prm.n_resp + q].x);
+  float L = 0.f, acc = 0.f;
+  for (int s = 0; s < prm.n_splits; ++s) {
+    const int64_t slot = ((int64_t)bh * prm.n_splits + s) * prm.n_resp + q;
+    const float2 ml = prm.part_ml[slot];
+    const float w = fast_exp2(ml.x - M);
+    L += w * ml.y;
+    acc += w * prm.part_o[slot * D + e];
+  }
+  const float v = acc / L;
+  char* orow = prm.O.row(b, h, q);
+  if (sizeof(T) == 2)
+    reinterpret_cast<uint16_t*>(orow)[e] = (uint16_t)f32_to_bf16_rne(v);
+  else
+    reinterpret_cast<float*>(orow)[e] = v;
+  if (prm.lse && e == 0) prm.lse[(int64_t)bh * prm.n_resp + q] = (M + __log2f(L)) * kLn2;
+}
+
+int attend_splits(const maskkv_desc* d, bool full) {
+  if (!full) return 1;
+  const int64_t qtiles = (d->n_resp + kQPerBlock - 1) / kQPerBlock;
+  const int64_t blocks = qtiles * d->B * d->H;
+  int64_t s = (1024 + blocks - 1) / blocks;
+  const int64_t by_len = ((int64_t)d->P_max + d->n_resp + 511) / 512;
+  if (s > by_len) s = by_len;
+  if (s > 64) s = 64;
+  if (s < 1) s = 1;
+  return (int)s;
+}
+
+template <typename T, int D>
+int launch_attend_t(const AttendParams& prm, int B, hipStream_t stream) {
+  const dim3 grid((prm.n_resp + kQPerBlock - 1) / kQPerBlock, prm.n_splits, B * prm.H);
+  hipLaunchKernelGGL((attend_kernel<T, D>), grid, dim3(kAttThreads), 0, stream, prm);
+  if (int e = check_launch("attend")) return e;
+  if (prm.n_splits > 1) {
+    hipLaunchKernelGGL((attend_merge_kernel<T, D>), dim3(prm.n_resp, B * prm.H), dim3(D), 0, stream, prm);
+    return check_launch("attend merge");
+  }
+  return MASKKV_OK;
+}
+
+}  // namespace
+
+size_t attend_workspace_bytes(const maskkv_desc* d, bool full) {
+  const int s = attend_splits(d, full);
+  if (s == 1) return 0;
+  const size_t rows = (size_t)d->B * d->H * s * d->n_resp;
+  return (rows * d->d * sizeof(float) + 255) / 256 * 256 + rows * sizeof(float2);
+}
+
+int launch_attend(const maskkv_desc* d, const Lens& lens, bool full, const View& Q, const void* Kc, const void* Vc,
+                  const int32_t* cu_budget, int64_t capacity, const View& K2, const View& V2, float scale,
+                  const View& O, float* lse, void* workspace, hipStream_t stream) {
+  AttendParams prm;
+  prm.Q = Q;
+  prm.K2 = K2;
+  prm.V2 = V2;
+  prm.O = O;
+  prm.lens = lens;
+  prm.Kc = reinterpret_cast<const char*>(Kc);
+  prm.Vc = reinterpret_cast<const char*>(Vc);
+  prm.cu = cu_budget;
+  prm.capacity = capacity;
+  prm.H = d->H;
+  prm.n_resp = d->n_resp;
+  prm.full = full ? 1 : 0;
+  prm.n_splits = attend_splits(d, full);
+  prm.c = scale * kLog2e;
+  prm.lse = lse;
+  prm.part_o = nullptr;
+  prm.part_ml = nullptr;
+  if (prm.n_splits > 1) {
+    const size_t rows = (size_t)d->B * d->H * prm.n_splits * d->n_resp;
+    prm.part_o = reinterpret_cast<float*>(workspace);
+    prm.part_ml = reinterpret_cast<float2*>(reinterpret_cast<char*>(workspace) +
+                                            (rows * d->d * sizeof(float) + 255) / 256 * 256);
+  }
+  if (d->dtype == MASKKV_BF16)
+    return d->d == 128 ? launch_attend_t<bf16_t, 128>(prm, d->B, stream) : launch_attend_t<bf16_t, 64>(prm, d->B, stream);
+  return d->d == 128 ? launch_attend_t<float, 128>(prm, d->B, stream) : launch_attend_t<float, 64>(prm, d->B, stream);
+}
+
+}  // namespace maskkv

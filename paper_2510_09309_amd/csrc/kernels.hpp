@@ -1,0 +1,31 @@
+// Internal launch interface between the C ABI (api.hip) and the kernel files.
+#pragma once
+
+#include "common.hpp"
+
+namespace maskkv {
+
+// score.hip
+size_t score_workspace_bytes(const maskkv_desc* d);
+int launch_score(const maskkv_desc* d, const View& Q, const View& K, const Lens& lens, float scale, float* scores,
+                 int64_t score_stride, float* prompt_mass, void* workspace, hipStream_t stream);
+
+// select.hip
+size_t select_workspace_bytes(const maskkv_desc* d);
+int launch_select(const maskkv_desc* d, const Lens& lens, const float* scores, int64_t score_stride, int window,
+                  int mode, const int32_t* budgets, int32_t* idx, int32_t* cu_budget, int64_t capacity,
+                  void* workspace, hipStream_t stream);
+int launch_head_budgets(const maskkv_desc* d, const float* prompt_mass, int32_t k_l, float alpha, int32_t* budgets,
+                        hipStream_t stream);
+
+// compact.hip
+int launch_compact(const maskkv_desc* d, const Lens& lens, const View& K, const View& V, const int32_t* idx, const int32_t* cu_budget,
+                   int64_t capacity, void* Kc, void* Vc, hipStream_t stream);
+
+// attend.hip
+size_t attend_workspace_bytes(const maskkv_desc* d, bool full);
+int launch_attend(const maskkv_desc* d, const Lens& lens, bool full, const View& Q, const void* Kc, const void* Vc,
+                  const int32_t* cu_budget, int64_t capacity, const View& K2, const View& V2, float scale,
+                  const View& O, float* lse, void* workspace, hipStream_t stream);
+
+}  // namespace maskkv

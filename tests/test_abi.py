@@ -1,0 +1,99 @@
+"""CPU-side checks of the C ABI: the library loads, exports every declared symbol, and validates arguments
+on the host before anything is launched (no GPU needed: every call here is rejected before a HIP call)."""
+import ctypes as ct
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "maskkv.h")
+
+
+@pytest.fixture(scope="module")
+def mk():
+    from paper_2510_09309_amd import binding
+    return binding
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(maskkv_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_four_named_calls():
+    names = declared_functions()
+    for n in ("maskkv_score", "maskkv_select", "maskkv_compact", "maskkv_attend"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol(mk):
+    lib = ct.CDLL(mk.LIB_PATH)
+    for name in declared_functions():
+        assert hasattr(lib, name), f"{name} declared in maskkv.h but not exported"
+    assert sorted(mk.SYMBOLS) == declared_functions()
+    assert mk.maskkv_version() == 1
+
+
+def test_strerror(mk):
+    lib = mk.raw_library()
+    assert lib.maskkv_strerror(0) == b"ok"
+    assert b"shape" in lib.maskkv_strerror(2)
+    assert b"unknown" in lib.maskkv_strerror(99)
+
+
+def test_workspace_sizes(mk):
+    d = mk.Desc(B=1, H=32, d=128, dtype=mk.MASKKV_BF16, n_resp=256, P_max=32768)
+    assert mk.maskkv_score_workspace_bytes(d) > 32 * 256 * 4
+    assert mk.maskkv_select_workspace_bytes(d) == 0
+    assert mk.maskkv_attend_workspace_bytes(d, False) == 0
+    assert mk.maskkv_attend_workspace_bytes(d, True) > 0
+    long = mk.Desc(B=2, H=4, d=128, dtype=mk.MASKKV_BF16, n_resp=8, P_max=100000)
+    assert mk.maskkv_select_workspace_bytes(long) == 2 * 4 * 100000 * 4
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(d=96), 2), (dict(dtype=7), 3), (dict(B=0), 2), (dict(B=65), 2), (dict(n_resp=0), 1),
+    (dict(P_max=-1), 1), (dict(prompt_len=[5000]), 1), (dict(H=0), 2),
+])
+def test_bad_descriptions_are_rejected(mk, kw, status):
+    base = dict(B=1, H=4, d=128, dtype=mk.MASKKV_BF16, n_resp=16, P_max=1024)
+    base.update(kw)
+    with pytest.raises(mk.MaskKVError) as e:
+        mk.maskkv_score_workspace_bytes(mk.Desc(**base))
+    assert e.value.status == status
+    assert mk.raw_library().maskkv_last_error() != b""
+
+
+def test_bad_call_arguments_are_rejected_before_launch(mk):
+    """Fake (never dereferenced) pointers: each call must fail in host validation."""
+    lib = mk.raw_library()
+    desc = mk.Desc(B=1, H=2, d=64, dtype=mk.MASKKV_F32, n_resp=8, P_max=100).c()
+    fake = 0x1000
+    good = mk._CTensor(fake, 0, 108 * 64, 64, None)
+    misaligned = mk._CTensor(fake + 4, 0, 108 * 64, 64, None)
+    short_row = mk._CTensor(fake, 0, 108 * 64, 32, None)
+    null = mk._CTensor(0, 0, 0, 64, None)
+    f = ct.c_void_p(fake)
+    call_score = lambda q, k, stride, ws, wsn: lib.maskkv_score(
+        ct.byref(desc), ct.byref(q), ct.byref(k), ct.c_float(0), f, ct.c_int64(stride), None, ws, ct.c_size_t(wsn), None)
+    assert call_score(null, good, 128, f, 1 << 20) == 1
+    assert call_score(good, misaligned, 128, f, 1 << 20) == 1
+    assert call_score(good, short_row, 128, f, 1 << 20) == 1
+    assert call_score(good, good, 64, f, 1 << 20) == 1          # score_stride < P_max
+    assert call_score(good, good, 128, None, 0) == 4            # no workspace
+    assert call_score(good, good, 128, f, 16) == 4              # too small
+    assert call_score(good, good, 128, ct.c_void_p(fake + 8), 1 << 20) == 4  # misaligned workspace
+    sel = lambda window, mode, cap: lib.maskkv_select(
+        ct.byref(desc), f, ct.c_int64(128), ct.c_int(window), ct.c_int(mode), f, f, f, ct.c_int64(cap), None,
+        ct.c_size_t(0), None)
+    assert sel(4, 0, 10) == 1      # even window
+    assert sel(0, 0, 10) == 1
+    assert sel(65, 0, 10) == 1
+    assert sel(7, 3, 10) == 1      # unknown pool mode
+    assert sel(7, 0, -1) == 1
+    assert lib.maskkv_compact(ct.byref(desc), ct.byref(good), ct.byref(good), f, None, ct.c_int64(4), f, f, None) == 1
+    assert lib.maskkv_head_budgets(ct.byref(desc), f, ct.c_int32(10), ct.c_float(1.5), f, None) == 1
+    assert lib.maskkv_head_budgets(ct.byref(desc), f, ct.c_int32(-1), ct.c_float(0.1), f, None) == 1
+    assert b"alpha" in lib.maskkv_last_error()
