@@ -248,7 +248,10 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const AttendParams 
         for (int qd = 0; qd < 4; ++qd) {
           u32x4 pf;
 #pragma unroll
-          for (int w = 0; w < 4; ++w) pf[w] = __builtin_bit_cast(uint32_t, s[kb][4 * qd + w]);
+          for (int w = 0; w < 4; ++w) {
+            const float pv = s[kb][4 * qd + w];
+            pf[w] = as_u32(pv);
+          }
 #pragma unroll
           for (int db = 0; db < C::kDB; ++db) {
             const u32x4 vf =

@@ -45,6 +45,11 @@ struct Lens {
 // 8ks+4g+q).  Both operands use the same map, so the contraction over the head dimension is exact.
 // Accumulator element i of lane (c = lane%32, g) is row 8*(i/4) + 4*g + i%4, column c.
 // ---------------------------------------------------------------------------------------------
+// Scalar bit reinterpretation by value.  (A bit_cast applied directly to a vector element expression
+// was observed to read element 0 for every index, so elements are always copied to a scalar first.)
+__device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
+
 template <typename T>
 __device__ __forceinline__ void mfma_step(const u32x4& a, const u32x4& b, f32x16& acc);
 
@@ -57,15 +62,16 @@ __device__ __forceinline__ void mfma_step<bf16_t>(const u32x4& a, const u32x4& b
 template <>
 __device__ __forceinline__ void mfma_step<float>(const u32x4& a, const u32x4& b, f32x16& acc) {
 #pragma unroll
-  for (int q = 0; q < 4; ++q)
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a[q]), __builtin_bit_cast(float, b[q]),
-                                               acc, 0, 0, 0);
+  for (int q = 0; q < 4; ++q) {
+    const uint32_t ua = a[q], ub = b[q];
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(as_f32(ua), as_f32(ub), acc, 0, 0, 0);
+  }
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
-  uint32_t u = __builtin_bit_cast(uint32_t, f);
+  uint32_t u = as_u32(f);
   u += 0x7FFFu + ((u >> 16) & 1u);
   return u >> 16;
 }
