@@ -1,0 +1,266 @@
+#!/usr/bin/env python3
+"""Benchmark of the MaskKV eviction hot path on one MI355X.
+
+One step = one layer of the headline long-context configuration (32 heads x head_dim 128, bf16,
+P = 32768 prompt tokens, 256 mask queries, 256 kept KV pairs per head on average with a 2:1
+per-head split, pool window 7) pushed through the whole path:
+    maskkv_score -> maskkv_select -> maskkv_compact -> maskkv_attend.
+Steps rotate over several resident layers with independent seeds so that nothing is served from
+cache by accident.  Inputs are synthetic (Gaussian with planted prompt positions), generated on
+the device before the timed region.
+
+Prints ONE JSON line: the metric (prompt tokens scored+evicted per second per layer, whole step),
+per-call timings, compressed- and full-cache attention TFLOP/s, a roofline object for the dominant
+kernel (score pass 2, timed with HIP events on the launch stream inside the timed region) and the
+CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as ct
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+HBM_PEAK_GBS = 8000.0
+
+WORKLOADS = {
+    # name: (H, d, P, n_m, avg budget, planted, layers resident)
+    "C4": dict(H=32, d=128, P=32768, n_m=256, budget_avg=256, n_planted=655, amplitude=2.5, window=7, seed=2000),
+    "C3": dict(H=32, d=128, P=8192, n_m=256, budget_avg=128, n_planted=164, amplitude=2.5, window=7, seed=1000),
+    "C2": dict(H=32, d=128, P=4096, n_m=256, budget_avg=256, n_planted=82, amplitude=2.5, window=7, seed=0),
+}
+
+
+class HipEvents:
+    """Raw HIP events (created through the HIP runtime already loaded by torch) for stage timing."""
+
+    def __init__(self):
+        path = None
+        with open("/proc/self/maps") as f:  # the HIP runtime instance torch and libmaskkv.so already share
+            for line in f:
+                if "libamdhip64" in line:
+                    path = line.split()[-1]
+                    break
+        assert path, "HIP runtime is not loaded"
+        self.hip = ct.CDLL(path)
+        self.hip.hipEventElapsedTime.argtypes = [ct.POINTER(ct.c_float), ct.c_void_p, ct.c_void_p]
+        self.hip.hipEventCreate.argtypes = [ct.POINTER(ct.c_void_p)]
+        self.hip.hipEventDestroy.argtypes = [ct.c_void_p]
+
+    def create(self) -> int:
+        ev = ct.c_void_p()
+        rc = self.hip.hipEventCreate(ct.byref(ev))
+        assert rc == 0, f"hipEventCreate failed: {rc}"
+        return ev.value
+
+    def elapsed_ms(self, a: int, b: int) -> float:
+        ms = ct.c_float()
+        rc = self.hip.hipEventElapsedTime(ct.byref(ms), ct.c_void_p(a), ct.c_void_p(b))
+        assert rc == 0, f"hipEventElapsedTime failed: {rc}"
+        return float(ms.value)
+
+    def destroy(self, ev: int) -> None:
+        self.hip.hipEventDestroy(ct.c_void_p(ev))
+
+
+def device_layer(torch, cfg, layer):
+    """Q [1,H,n_m,d], K, V [1,H,N,d] bf16 on the device: Gaussian / sqrt(d), unit direction u_h added to all
+    mask queries, amplitude*u_h added to n_planted random prompt keys per head (same recipe as synth.make_layer)."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(cfg["seed"] + layer)
+    H, d, P, n_m = cfg["H"], cfg["d"], cfg["P"], cfg["n_m"]
+    N = P + n_m
+    s = 1.0 / d ** 0.5
+    Q = torch.randn((1, H, n_m, d), generator=g, device="cuda", dtype=torch.float32) * s
+    K = torch.randn((1, H, N, d), generator=g, device="cuda", dtype=torch.float32) * s
+    V = torch.randn((1, H, N, d), generator=g, device="cuda", dtype=torch.float32) * s
+    u = torch.randn((H, d), generator=g, device="cuda", dtype=torch.float32)
+    u = u / u.norm(dim=1, keepdim=True)
+    Q += u[None, :, None, :]
+    for h in range(H):
+        pos = torch.randperm(P, generator=g, device="cuda")[:cfg["n_planted"]]
+        K[0, h, pos] += cfg["amplitude"] * u[h]
+    return Q.to(torch.bfloat16), K.to(torch.bfloat16), V.to(torch.bfloat16)
+
+
+def cpu_oracle_baseline(cfg, budget_seconds=15.0):
+    """Time the float64 oracle (score+pool+select+compact+attend) head by head on the host cores."""
+    import torch
+    from oracle import maskkv_oracle as orc
+    from paper_2510_09309_amd import synth
+    H_sample = 4
+    L = synth.make_layer(cfg["seed"], H=H_sample, d=cfg["d"], P=cfg["P"], n_m=cfg["n_m"], dtype="bf16",
+                         n_planted=cfg["n_planted"], amplitude=cfg["amplitude"])
+    budgets = synth.budgets_two_level(cfg["H"], cfg["budget_avg"], seed=cfg["seed"] + 7)
+    done, t0 = 0, time.perf_counter()
+    while True:
+        h = done % H_sample
+        I, _ = orc.score(L.Q[h], L.K[h], L.P)
+        keep = orc.select(orc.pool(I, cfg["window"]), int(budgets[done % cfg["H"]]))
+        Kc, Vc = orc.compact(L.K[h, :L.P], L.V[h, :L.P], keep)
+        orc.attend(L.Q[h], Kc, Vc, L.K[h, L.P:], L.V[h, L.P:])
+        done += 1
+        el = time.perf_counter() - t0
+        if el >= budget_seconds:
+            break
+    per_layer = el / done * cfg["H"]
+    return {
+        "value": cfg["P"] / per_layer, "unit": "prompt tokens/s per layer", "cores": int(torch.get_num_threads()),
+        "kind": "oracle",
+        "sample": f"{done} head passes (score+pool+select+compact+attend, float64 numpy) of the same workload in "
+                  f"{el:.1f} s; one layer = {cfg['H']} heads -> {per_layer:.2f} s/layer",
+        "host_cpu_count": os.cpu_count(),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="C4", choices=sorted(WORKLOADS))
+    ap.add_argument("--resident-layers", type=int, default=4)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures the hot path on ONE GPU; --gpus must be 1 "
+              "(the path is independent per head and needs no collective, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2510_09309_amd import binding as mk, synth
+
+    cfg = WORKLOADS[args.workload]
+    H, d, P, n_m = cfg["H"], cfg["d"], cfg["P"], cfg["n_m"]
+    N = P + n_m
+    torch.cuda.set_device(0)
+    desc = mk.Desc(B=1, H=H, d=d, dtype=mk.MASKKV_BF16, n_resp=n_m, P_max=P)
+    budgets_h = synth.budgets_two_level(H, cfg["budget_avg"], seed=cfg["seed"] + 7)
+    cap = int(budgets_h.sum())
+    budgets = torch.from_numpy(budgets_h).cuda()
+
+    layers = [device_layer(torch, cfg, l) for l in range(args.resident_layers)]
+    resp = [(mk.tensor_view(K, seq_start=[P]), mk.tensor_view(V, seq_start=[P])) for (_, K, V) in layers]
+    stride = (P + 63) // 64 * 64
+    scores = torch.empty((H, stride), dtype=torch.float32, device="cuda")
+    mass = torch.empty(H, dtype=torch.float32, device="cuda")
+    idx = torch.empty(cap, dtype=torch.int32, device="cuda")
+    cu = torch.empty(H + 1, dtype=torch.int32, device="cuda")
+    Kc = torch.empty((cap, d), dtype=torch.bfloat16, device="cuda")
+    Vc = torch.empty_like(Kc)
+    O = torch.empty((1, H, n_m, d), dtype=torch.bfloat16, device="cuda")
+    Of = torch.empty_like(O)
+
+    def ws(n):
+        return torch.empty(max(n, 256), dtype=torch.uint8, device="cuda")
+    ws_score = ws(mk.maskkv_score_workspace_bytes(desc))
+    ws_sel = ws(mk.maskkv_select_workspace_bytes(desc))
+    ws_att = ws(mk.maskkv_attend_workspace_bytes(desc, False))
+    ws_full = ws(mk.maskkv_attend_workspace_bytes(desc, True))
+
+    hev = HipEvents()
+    stream = torch.cuda.current_stream()
+
+    def step(i, events=(0, 0, 0, 0)):
+        Q, K, V = layers[i % len(layers)]
+        Kr, Vr = resp[i % len(layers)]
+        mk.maskkv_score_profiled(desc, Q, K, 0.0, scores, stride, mass, ws_score, events, stream)
+        mk.maskkv_select(desc, scores, stride, cfg["window"], mk.POOL_MEAN, budgets, idx, cu, cap, ws_sel, stream)
+        mk.maskkv_compact(desc, K, V, idx, cu, cap, Kc, Vc, stream)
+        mk.maskkv_attend(desc, Q, Kc, Vc, cu, cap, Kr, Vr, 0.0, O, None, ws_att, stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    # ---- the timed region: exactly --steps whole-path steps; score pass 2 is bracketed by HIP events
+    ev = [(hev.create(), hev.create()) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, (0, 0, ev[i][0], ev[i][1]))
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    pass2_ms = float(np.mean([hev.elapsed_ms(a, b) for a, b in ev]))
+    for a, b in ev:
+        hev.destroy(a)
+        hev.destroy(b)
+
+    # ---- per-call breakdown (outside the timed region, same rotation), torch events on the same stream
+    def time_call(fn, reps):
+        for i in range(3):
+            fn(i)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record(stream)
+        for i in range(reps):
+            fn(i)
+        b.record(stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    reps = max(8, args.steps // 2)
+    t_score = time_call(lambda i: mk.maskkv_score(desc, layers[i % len(layers)][0], layers[i % len(layers)][1], 0.0,
+                                                  scores, stride, mass, ws_score, stream), reps)
+    t_select = time_call(lambda i: mk.maskkv_select(desc, scores, stride, cfg["window"], mk.POOL_MEAN, budgets, idx,
+                                                    cu, cap, ws_sel, stream), reps)
+    t_compact = time_call(lambda i: mk.maskkv_compact(desc, layers[i % len(layers)][1], layers[i % len(layers)][2],
+                                                      idx, cu, cap, Kc, Vc, stream), reps)
+    t_attend = time_call(lambda i: mk.maskkv_attend(desc, layers[i % len(layers)][0], Kc, Vc, cu, cap,
+                                                    resp[i % len(layers)][0], resp[i % len(layers)][1], 0.0, O, None,
+                                                    ws_att, stream), reps)
+    t_full = time_call(lambda i: mk.maskkv_attend_full(desc, layers[i % len(layers)][0], layers[i % len(layers)][1],
+                                                       layers[i % len(layers)][2], 0.0, Of, None, ws_full, stream),
+                       max(4, reps // 4))
+
+    keys_compressed = cap + H * n_m
+    flop_attend = 4.0 * n_m * d * keys_compressed
+    flop_full = 4.0 * n_m * d * N * H
+    flop_qk_prompt = 2.0 * n_m * d * P * H           # one QK^T over the prompt keys: what pass 2 needs
+    flop_qk_all = 2.0 * n_m * d * N * H              # one QK^T over all keys: the method's scoring work
+    bytes_k = 2.0 * N * d * H                        # K read once, bf16
+    bytes_gather = 2.0 * 2 * cap * d * 2             # K and V rows, read + write
+
+    out = {
+        "metric": "prompt tokens scored+evicted/s per layer; compressed-attn TFLOP/s @32k prompt",
+        "value": P / (ms_per_step * 1e-3),
+        "unit": "prompt tokens/s per layer (score+select+compact+attend, all 32 heads)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: 1 sequence, {H} heads x {d}, bf16, P={P}, {n_m} mask queries, "
+                               f"budget {cfg['budget_avg']}/head avg (2:1 split), pool window {cfg['window']}; "
+                               f"one layer per step, {len(layers)} resident layers rotated",
+                   "global_batch": 1, "seq_len": N},
+        "breakdown_ms": {"score": t_score, "select": t_select, "compact": t_compact, "attend": t_attend,
+                         "attend_full": t_full, "score_pass2_in_timed_region": pass2_ms},
+        "tokens_scored_evicted_per_s": P / ((t_score + t_select + t_compact) * 1e-3),
+        "attend_compressed_tflops": flop_attend / (t_attend * 1e-3) / 1e12,
+        "attend_full_tflops": flop_full / (t_full * 1e-3) / 1e12,
+        "attend_speedup_full_over_compressed": t_full / t_attend,
+        "score_step_tflops_algorithmic": flop_qk_all / (t_score * 1e-3) / 1e12,
+        "score_k_read_gbs_algorithmic": bytes_k / (t_score * 1e-3) / 1e9,
+        "gather_gbs": bytes_gather / (t_compact * 1e-3) / 1e9,
+        "roofline": {
+            "kernel": "score_kernel<bf16,128,pass 2> (QK^T over the prompt keys + exp + column sums)",
+            "bound": "mfma", "achieved": flop_qk_prompt / (pass2_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": flop_qk_prompt / (pass2_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "traffic": None,
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_oracle_baseline(cfg)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -115,6 +115,16 @@ int maskkv_score(const maskkv_desc* desc, const maskkv_tensor* Q_mask, const mas
                  float scale, float* scores, int64_t score_stride, float* prompt_mass,
                  void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * maskkv_score with timing marks.  events: HOST array of 4 hipEvent_t (each may be NULL), created by
+ * the caller with timing enabled; they are recorded on the stream before pass 1 (row statistics),
+ * before the merge, before pass 2 (column sums) and after pass 2.  Same result as maskkv_score.
+ * For profiling harnesses; Section 3.3 Stage 1 as above.
+ */
+int maskkv_score_profiled(const maskkv_desc* desc, const maskkv_tensor* Q_mask, const maskkv_tensor* K_full,
+                          float scale, float* scores, int64_t score_stride, float* prompt_mass,
+                          void* workspace, size_t workspace_bytes, void* stream, void* const* events);
+
 /* Workspace (DEVICE bytes) needed by maskkv_select (may be 0). 256-byte alignment. */
 int maskkv_select_workspace_bytes(const maskkv_desc* desc, size_t* bytes);
 

@@ -23,7 +23,7 @@ MAX_BATCH = 64
 
 SYMBOLS = [
     "maskkv_version", "maskkv_strerror", "maskkv_last_error",
-    "maskkv_score_workspace_bytes", "maskkv_score",
+    "maskkv_score_workspace_bytes", "maskkv_score", "maskkv_score_profiled",
     "maskkv_select_workspace_bytes", "maskkv_select",
     "maskkv_compact",
     "maskkv_attend_workspace_bytes", "maskkv_attend", "maskkv_attend_full",
@@ -159,6 +159,18 @@ def maskkv_score(desc: Desc, Q_mask, K_full, scale: float, scores: torch.Tensor,
     wp, wn = _ws(workspace)
     _check(_lib.maskkv_score(ct.byref(desc.c()), ct.byref(q), ct.byref(k), ct.c_float(scale), _ptr(scores),
                              ct.c_int64(score_stride), _ptr(prompt_mass), wp, wn, _stream(stream)), "maskkv_score")
+
+
+def maskkv_score_profiled(desc: Desc, Q_mask, K_full, scale: float, scores: torch.Tensor, score_stride: int,
+                          prompt_mass: Optional[torch.Tensor], workspace: Optional[torch.Tensor], events: Sequence[int],
+                          stream=None) -> None:
+    """``events``: four raw hipEvent_t handles (0 to skip one), recorded at the stage boundaries."""
+    q, k = _as_view(Q_mask), _as_view(K_full)
+    wp, wn = _ws(workspace)
+    ev = (ct.c_void_p * 4)(*[ct.c_void_p(int(e)) for e in events])
+    _check(_lib.maskkv_score_profiled(ct.byref(desc.c()), ct.byref(q), ct.byref(k), ct.c_float(scale), _ptr(scores),
+                                      ct.c_int64(score_stride), _ptr(prompt_mass), wp, wn, _stream(stream), ev),
+           "maskkv_score_profiled")
 
 
 def maskkv_select(desc: Desc, scores: torch.Tensor, score_stride: int, pool_window: int, pool_mode: int,

@@ -153,6 +153,13 @@ int maskkv_score_workspace_bytes(const maskkv_desc* desc, size_t* bytes) {
 int maskkv_score(const maskkv_desc* desc, const maskkv_tensor* Q_mask, const maskkv_tensor* K_full, float scale,
                  float* scores, int64_t score_stride, float* prompt_mass, void* workspace, size_t workspace_bytes,
                  void* stream) {
+  return maskkv_score_profiled(desc, Q_mask, K_full, scale, scores, score_stride, prompt_mass, workspace,
+                               workspace_bytes, stream, nullptr);
+}
+
+int maskkv_score_profiled(const maskkv_desc* desc, const maskkv_tensor* Q_mask, const maskkv_tensor* K_full,
+                          float scale, float* scores, int64_t score_stride, float* prompt_mass, void* workspace,
+                          size_t workspace_bytes, void* stream, void* const* events) {
   Lens lens;
   View q, k;
   if (int e = check_desc(desc, &lens)) return e;
@@ -164,7 +171,7 @@ int maskkv_score(const maskkv_desc* desc, const maskkv_tensor* Q_mask, const mas
   }
   if (int e = check_workspace("score", workspace, workspace_bytes, score_workspace_bytes(desc))) return e;
   return launch_score(desc, q, k, lens, pick_scale(desc, scale), scores, score_stride, prompt_mass, workspace,
-                      reinterpret_cast<hipStream_t>(stream));
+                      reinterpret_cast<hipStream_t>(stream), events);
 }
 
 int maskkv_select_workspace_bytes(const maskkv_desc* desc, size_t* bytes) {

@@ -8,7 +8,8 @@ namespace maskkv {
 // score.hip
 size_t score_workspace_bytes(const maskkv_desc* d);
 int launch_score(const maskkv_desc* d, const View& Q, const View& K, const Lens& lens, float scale, float* scores,
-                 int64_t score_stride, float* prompt_mass, void* workspace, hipStream_t stream);
+                 int64_t score_stride, float* prompt_mass, void* workspace, hipStream_t stream,
+                 void* const* events);
 
 // select.hip
 size_t select_workspace_bytes(const maskkv_desc* d);

@@ -284,21 +284,34 @@ int score_chunk_keys(const maskkv_desc* d) {
   return (int)c;
 }
 
+int mark(void* const* events, int i, hipStream_t stream) {
+  if (!events || !events[i]) return MASKKV_OK;
+  const hipError_t e = hipEventRecord(reinterpret_cast<hipEvent_t>(events[i]), stream);
+  if (e == hipSuccess) return MASKKV_OK;
+  set_error("score: hipEventRecord(events[%d]): %s", i, hipGetErrorString(e));
+  return MASKKV_EHIP;
+}
+
 template <typename T, int D>
-int launch_score_t(const ScoreParams& prm, int B, hipStream_t stream) {
+int launch_score_t(const ScoreParams& prm, int B, hipStream_t stream, void* const* events) {
   const dim3 block(kScoreThreads);
   const dim3 grid1(prm.nch_max, B * prm.H);
+  if (int e = mark(events, 0, stream)) return e;
   hipLaunchKernelGGL((score_kernel<T, D, 1>), grid1, block, 0, stream, prm);
   if (int e = check_launch("score pass 1")) return e;
+  if (int e = mark(events, 1, stream)) return e;
   hipLaunchKernelGGL(score_merge_kernel, dim3(B * prm.H), dim3(256), 0, stream, prm);
   if (int e = check_launch("score merge")) return e;
+  if (int e = mark(events, 2, stream)) return e;
   int npc_max = 0;
   for (int b = 0; b < B; ++b) npc_max = max(npc_max, (prm.lens.P[b] + prm.chunk - 1) / prm.chunk);
-  if (npc_max == 0) return MASKKV_OK;
-  const dim3 grid2(npc_max, B * prm.H);
-  const size_t dyn = sizeof(float) * kScoreWaves * prm.chunk;
-  hipLaunchKernelGGL((score_kernel<T, D, 2>), grid2, block, dyn, stream, prm);
-  return check_launch("score pass 2");
+  if (npc_max > 0) {
+    const dim3 grid2(npc_max, B * prm.H);
+    const size_t dyn = sizeof(float) * kScoreWaves * prm.chunk;
+    hipLaunchKernelGGL((score_kernel<T, D, 2>), grid2, block, dyn, stream, prm);
+    if (int e = check_launch("score pass 2")) return e;
+  }
+  return mark(events, 3, stream);
 }
 
 }  // namespace
@@ -314,7 +327,8 @@ size_t score_workspace_bytes(const maskkv_desc* d) {
 }
 
 int launch_score(const maskkv_desc* d, const View& Q, const View& K, const Lens& lens, float scale, float* scores,
-                 int64_t score_stride, float* prompt_mass, void* workspace, hipStream_t stream) {
+                 int64_t score_stride, float* prompt_mass, void* workspace, hipStream_t stream,
+                 void* const* events) {
   ScoreParams prm;
   prm.Q = Q;
   prm.K = K;
@@ -334,9 +348,9 @@ int launch_score(const maskkv_desc* d, const View& Q, const View& K, const Lens&
   prm.score_stride = score_stride;
   prm.prompt_mass = prompt_mass;
   if (d->dtype == MASKKV_BF16) {
-    return d->d == 128 ? launch_score_t<bf16_t, 128>(prm, d->B, stream) : launch_score_t<bf16_t, 64>(prm, d->B, stream);
+    return d->d == 128 ? launch_score_t<bf16_t, 128>(prm, d->B, stream, events) : launch_score_t<bf16_t, 64>(prm, d->B, stream, events);
   }
-  return d->d == 128 ? launch_score_t<float, 128>(prm, d->B, stream) : launch_score_t<float, 64>(prm, d->B, stream);
+  return d->d == 128 ? launch_score_t<float, 128>(prm, d->B, stream, events) : launch_score_t<float, 64>(prm, d->B, stream, events);
 }
 
 }  // namespace maskkv

@@ -1,0 +1,124 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times (needs an MI355X).
+
+One layer of the headline configuration (32 heads x 128, bf16, P = 32768, 256 mask queries, budgets
+341/171, window 7) is pushed through the C ABI exactly as bench.py does; the oracle then checks a
+sample of heads element by element (scores, kept sets, gathered rows, attention rows) and
+size-independent properties on all heads.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import maskkv_oracle as orc
+from paper_2510_09309_amd import synth
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def c4_layer():
+    cfg = synth.CONFIGS["C4"]
+    L = synth.config_layer("C4", layer=0)
+    batch = hp.Batch([L])
+    budgets = synth.config_budgets("C4")
+    assert budgets.sum() == 32 * 256
+    scores, mass = hp.gpu_score(batch)
+    idx, cu, cap = hp.gpu_select(batch, scores, budgets, cfg["window"])
+    Kc, Vc = hp.gpu_compact(batch, idx, cu, cap)
+    O, lse = hp.gpu_attend(batch, Kc, Vc, cu, cap)
+    Of, lsef = hp.gpu_attend_full(batch)
+    return dict(cfg=cfg, L=L, batch=batch, budgets=budgets, scores=scores, mass=mass, idx=idx, cu=cu, cap=cap,
+                Kc=Kc, Vc=Vc, O=O, Of=Of, lse=lse, lsef=lsef)
+
+
+SAMPLE_HEADS = [0, 13, 31]
+
+
+def test_c4_scores_sampled_heads(c4_layer):
+    s = c4_layer
+    worst = hp.check_scores(s["batch"], s["scores"], s["mass"], heads=SAMPLE_HEADS)
+    assert worst < 1e-4
+
+
+def test_c4_score_properties_all_heads(c4_layer):
+    """Any size: scores positive, prompt mass = sum of scores, 0 < mass < n_m."""
+    s = c4_layer
+    L = s["L"]
+    sc = s["scores"][:, :L.P].double()
+    assert torch.isfinite(sc).all() and (sc > 0).all()
+    mass = s["mass"].double()
+    assert torch.allclose(sc.sum(dim=1), mass, rtol=1e-5)
+    assert (mass > 0).all() and (mass < L.n_m).all()
+
+
+def test_c4_select_compact_sampled_heads(c4_layer):
+    s = c4_layer
+    L, cfg = s["L"], s["cfg"]
+    keeps, cu_h = hp.split_idx(s["idx"], s["cu"])
+    assert cu_h.tolist() == np.concatenate([[0], np.cumsum(s["budgets"])]).tolist()
+    Kc_h, Vc_h = s["Kc"].float().cpu().numpy(), s["Vc"].float().cpu().numpy()
+    sc = s["scores"].cpu().numpy()
+    for h in range(L.H):
+        keep = keeps[h]
+        assert keep.shape[0] == s["budgets"][h] and np.all(np.diff(keep) > 0) and keep[0] >= 0 and keep[-1] < L.P
+        # bit-exact against the oracle's fp32-precision decision on the GPU's own scores (all heads)
+        ref = orc.select(orc.pool(sc[h, :L.P], cfg["window"], dtype=np.float32), int(s["budgets"][h]))
+        assert np.array_equal(keep, ref)
+        assert np.array_equal(Kc_h[cu_h[h]:cu_h[h + 1]], L.K[h, keep])
+        assert np.array_equal(Vc_h[cu_h[h]:cu_h[h + 1]], L.V[h, keep])
+    for h in SAMPLE_HEADS:
+        I, _ = orc.score(L.Q[h], L.K[h], L.P)
+        hp.check_keep_against_oracle(orc.pool(I, cfg["window"]), int(s["budgets"][h]), keeps[h], f"h{h}")
+        near = {p + t for p in L.planted[h].tolist() for t in range(-3, 4)}
+        assert set(keeps[h].tolist()) <= near, "kept tokens must sit on planted positions (dilated by the window)"
+
+
+def test_c4_attention_sampled_heads(c4_layer):
+    s = c4_layer
+    L = s["L"]
+    keeps, _ = hp.split_idx(s["idx"], s["cu"])
+    O, Of = s["O"].float().cpu().numpy(), s["Of"].float().cpu().numpy()
+    lse = s["lse"].cpu().numpy().reshape(L.H, L.n_m)
+    lsef = s["lsef"].cpu().numpy().reshape(L.H, L.n_m)
+    for h in SAMPLE_HEADS:
+        keep = keeps[h]
+        ref, rl = orc.attend(L.Q[h], L.K[h, keep], L.V[h, keep], L.K[h, L.P:], L.V[h, L.P:], return_lse=True)
+        assert np.abs(O[0, h] - ref).max() <= hp.ATTEND_ATOL_BF16
+        assert np.abs(lse[h] - rl).max() < 1e-3
+        reff, rlf = orc.attend_full(L.Q[h], L.K[h], L.V[h], return_lse=True)
+        assert np.abs(Of[0, h] - reff).max() <= hp.ATTEND_ATOL_BF16
+        assert np.abs(lsef[h] - rlf).max() < 1e-3
+
+
+def test_c5_shaped_ragged_batch_reduced():
+    """Batched ragged case at reduced batch: 3 sequences, prompts in 4k-16k, 512 mask queries, log-uniform budgets;
+    compress once, then two denoising steps with fresh response Q/K/V over the fixed compressed cache."""
+    m = hp.mk()
+    cfg = synth.CONFIGS["C5"]
+    H = 4
+    Ps = [4096, 16384, 9001]
+    layers = [synth.make_layer(3100 + b, H=H, d=128, P=P, n_m=512, dtype="bf16", n_planted=int(0.02 * P), amplitude=2.5)
+              for b, P in enumerate(Ps)]
+    batch = hp.Batch(layers)
+    budgets = synth.budgets_log_uniform(len(Ps) * H, 64, 1024, seed=3007)
+    scores, mass = hp.gpu_score(batch)
+    hp.check_scores(batch, scores, mass, heads=[0, 3])
+    idx, cu, cap = hp.gpu_select(batch, scores, budgets, 7)
+    keeps, cu_h = hp.split_idx(idx, cu)
+    Kc, Vc = hp.gpu_compact(batch, idx, cu, cap)
+    for step in range(2):
+        qkv = [synth.make_response_step(3001 + 10 * step + b, H, 128, 512) for b in range(len(Ps))]
+        Qr = hp.upload(np.stack([x[0] for x in qkv]), "bf16")
+        Kr = hp.upload(np.stack([x[1] for x in qkv]), "bf16")
+        Vr = hp.upload(np.stack([x[2] for x in qkv]), "bf16")
+        O, _ = hp.gpu_attend(batch, Kc, Vc, cu, cap, Q=Qr, Kr=Kr, Vr=Vr)
+        for b, L in enumerate(layers):
+            for h in (0, 3):
+                keep = keeps[b * H + h]
+                ref = orc.attend(qkv[b][0][h], L.K[h, keep], L.V[h, keep], qkv[b][1][h], qkv[b][2][h])
+                assert np.abs(O[b, h].float().cpu().numpy() - ref).max() <= hp.ATTEND_ATOL_BF16
+    for b, L in enumerate(layers):
+        for h in (0, 3):
+            I, _ = orc.score(L.Q[h], L.K[h], L.P)
+            hp.check_keep_against_oracle(orc.pool(I, 7), int(budgets[b * H + h]), keeps[b * H + h], f"b{b} h{h}")
