@@ -96,8 +96,9 @@ const char* maskkv_last_error(void);
 
 /*
  * Workspace (DEVICE bytes) needed by maskkv_score for this description.  The workspace
- * holds per-key-chunk softmax row statistics between the two passes; contents are
- * scratch.  256-byte alignment is required.
+ * holds per-key-segment softmax row statistics between the two passes; contents are
+ * scratch.  The size depends on prompt_len: query it with the description the call will
+ * use.  256-byte alignment is required.
  */
 int maskkv_score_workspace_bytes(const maskkv_desc* desc, size_t* bytes);
 

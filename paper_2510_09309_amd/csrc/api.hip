@@ -146,7 +146,7 @@ int maskkv_score_workspace_bytes(const maskkv_desc* desc, size_t* bytes) {
     set_error("bytes is NULL");
     return MASKKV_EINVAL;
   }
-  *bytes = score_workspace_bytes(desc);
+  *bytes = score_workspace_bytes(desc, lens);
   return MASKKV_OK;
 }
 
@@ -169,7 +169,7 @@ int maskkv_score_profiled(const maskkv_desc* desc, const maskkv_tensor* Q_mask, 
     set_error("scores is NULL or score_stride %lld < P_max %d", (long long)score_stride, desc->P_max);
     return MASKKV_EINVAL;
   }
-  if (int e = check_workspace("score", workspace, workspace_bytes, score_workspace_bytes(desc))) return e;
+  if (int e = check_workspace("score", workspace, workspace_bytes, score_workspace_bytes(desc, lens))) return e;
   return launch_score(desc, q, k, lens, pick_scale(desc, scale), scores, score_stride, prompt_mass, workspace,
                       reinterpret_cast<hipStream_t>(stream), events);
 }

@@ -2,16 +2,21 @@
 //   A = softmax_row(Q_mask K_full^T * scale),  I_j = sum_i A_ij over the prompt columns.
 //
 // A column sum needs every row's final softmax normaliser, so the logits are formed twice:
-//   pass 1  row statistics (running max and sum of exponentials, base 2) per key chunk,
-//   merge   per-row log-sum-exp over the chunks (+ the prompt's share of each row = prompt mass),
+//   pass 1  row statistics (reference exponent and sum of exponentials, base 2) per key segment,
+//   merge   per-row log-sum-exp over the segments (+ the prompt's share of each row = prompt mass),
 //   pass 2  logits again, p = exp2(s*c - lse), summed over the queries for every prompt key.
 // Storing the n_m x N logits instead would cost far more HBM traffic than the second MFMA pass.
 //
-// Tiling: one workgroup = 4 waves = one key chunk of one (b, h).  Each wave keeps 64 queries as MFMA
-// operands in registers; 64-key tiles of K stream through a padded, double-buffered LDS tile shared by
-// the four waves.  Pass 1 puts keys on the MFMA row axis so that a lane owns one query and the softmax
-// statistics never leave the lane; pass 2 puts queries on the row axis so that the sum over queries is
-// in-lane adds plus one cross-lane exchange.
+// Work decomposition: the key axis of every (b, h) is cut into 64-key tiles (prompt tiles, then response
+// tiles; a tile never straddles the prompt/response boundary).  All tiles of the launch form one global
+// index space that is divided evenly over a grid of about two workgroups per compute unit, so every
+// workgroup streams the same number of tiles whatever the batch raggedness.  A workgroup walks its range
+// as "segments" (maximal runs inside one region of one head).
+//
+// Tiling: one workgroup = 4 waves; each wave keeps 64 queries as MFMA operands in registers; K tiles
+// stream through a padded, double-buffered LDS tile shared by the four waves.  Pass 1 puts keys on the
+// MFMA row axis so that a lane owns one query and the softmax statistics never leave the lane; pass 2
+// puts queries on the row axis so that the sum over queries is in-lane adds plus one cross-lane exchange.
 #include "kernels.hpp"
 
 namespace maskkv {
@@ -21,7 +26,9 @@ namespace {
 constexpr int kScoreThreads = 256;
 constexpr int kScoreWaves = 4;
 constexpr int kQPerWave = 64;                          // two 32-row MFMA blocks
-constexpr int kQPerGroup = kScoreWaves * kQPerWave;    // queries covered per sweep of the chunk
+constexpr int kQPerGroup = kScoreWaves * kQPerWave;    // queries covered per sweep of a segment
+constexpr int kTargetGroups = 512;                     // about two resident workgroups per compute unit
+constexpr float kLazyLimit = 1.152921504606847e18f;    // 2^60: pass 1 re-centres its reference beyond this
 
 template <typename T, int D>
 struct ScoreCfg {
@@ -33,51 +40,43 @@ struct ScoreCfg {
   static constexpr int kPiecesPerRow = kRowB / 16;
 };
 
+// Tile bookkeeping of one pass, computed on the host.
+struct TileMap {
+  int tk;                         // keys per tile
+  int with_resp;                  // 1: response tiles are part of the index space (pass 1)
+  int R;                          // tiles per workgroup
+  int T;                          // tiles in total
+  int toff[MASKKV_MAX_BATCH + 1]; // first global tile of sequence b (all its heads)
+};
+
 struct ScoreParams {
   View Q, K;
   Lens lens;
-  int H, n_resp, n_query;
-  int chunk;          // keys per chunk (multiple of the tile)
-  int nch_max;        // chunk slots per (b, h) in the statistics buffer
+  TileMap map;        // of the pass being launched
+  TileMap map1;       // of pass 1 (the merge kernel needs it to find the partial statistics)
+  int B, H, n_resp, n_query;
+  int parts_p, parts_r;  // partial-statistics slots per (b, h): prompt region, response region
   float c;            // scale * log2(e)
-  float2* stats;      // [B*H][nch_max][n_query] (max, sum) in the base-2 domain
+  float2* stats;      // [B*H][parts_p + parts_r][n_query] (reference, sum) in the base-2 domain
   float* lse2;        // [B*H][n_query]
   float* scores;      // [B*H][score_stride]
   int64_t score_stride;
   float* prompt_mass; // [B*H] or null
 };
 
-// Key range of chunk slot `ch` for a sequence with P prompt keys: prompt chunks first, then response chunks.
-// Chunks never straddle the prompt/response boundary.  Returns false for an unused slot.
-__device__ __forceinline__ bool chunk_range(int ch, int P, int n_resp, int chunk, int& k0, int& k1, bool& is_prompt) {
-  const int npc = (P + chunk - 1) / chunk;
-  const int nrc = (n_resp + chunk - 1) / chunk;
-  if (ch < npc) {
-    k0 = ch * chunk;
-    k1 = min(P, k0 + chunk);
-    is_prompt = true;
-    return true;
-  }
-  const int rc = ch - npc;
-  if (rc < nrc) {
-    k0 = P + rc * chunk;
-    k1 = min(P + n_resp, k0 + chunk);
-    is_prompt = false;
-    return true;
-  }
-  return false;
-}
+__device__ __forceinline__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 template <typename T, int D>
-__device__ __forceinline__ void load_tile_global(const View& K, int b, int h, int key0, int klast, u32x4 (&regs)[ScoreCfg<T, D>::kPieces]) {
+__device__ __forceinline__ void load_tile_global(const char* kbase, int64_t stride_t, int key0, int klast,
+                                                 u32x4 (&regs)[ScoreCfg<T, D>::kPieces]) {
   using C = ScoreCfg<T, D>;
 #pragma unroll
   for (int i = 0; i < C::kPieces; ++i) {
     const int p = threadIdx.x + i * kScoreThreads;
     const int row = p / C::kPiecesPerRow;
     const int col = p % C::kPiecesPerRow;
-    const int key = min(key0 + row, klast);  // rows past the chunk end re-read the last valid row
-    regs[i] = *reinterpret_cast<const u32x4*>(K.row(b, h, key) + col * 16);
+    const int key = min(key0 + row, klast);  // rows past the segment end re-read its last valid row
+    regs[i] = *reinterpret_cast<const u32x4*>(kbase + (int64_t)key * stride_t + col * 16);
   }
 }
 
@@ -98,170 +97,214 @@ template <typename T, int D, int PASS>
 __global__ __launch_bounds__(kScoreThreads) void score_kernel(const ScoreParams prm) {
   using C = ScoreCfg<T, D>;
   __shared__ __attribute__((aligned(16))) char kt[2][C::kTK * C::kRowP];
-  extern __shared__ __attribute__((aligned(16))) float colsum[];  // pass 2: [kScoreWaves][chunk]
-
-  const int bh = blockIdx.y;
-  const int b = bh / prm.H;
-  const int h = bh % prm.H;
-  const int P = prm.lens.P[b];
-  int k0, k1;
-  bool is_prompt;
-  if (!chunk_range(blockIdx.x, P, prm.n_resp, prm.chunk, k0, k1, is_prompt)) return;
-  if (PASS == 2 && !is_prompt) return;
+  __shared__ float cs[2][kScoreWaves][C::kTK];  // pass 2: per-wave column partials of the last two tiles
+  __shared__ float nlse[kQPerGroup];            // pass 2: -lse2 of the current query group
 
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int r = lane & 31;
   const int g = lane >> 5;
-  const int ntiles = (k1 - k0 + C::kTK - 1) / C::kTK;
   const float c = prm.c;
+  const TileMap& map = prm.map;
 
-  for (int qg = 0; qg < prm.n_query; qg += kQPerGroup) {
-    const int q0 = qg + wave * kQPerWave;
-    // Query fragments stay in registers for the whole chunk.
-    u32x4 qf[2][C::kSteps];
+  int s = blockIdx.x * map.R;
+  const int e = min(map.T, s + map.R);
+  int cur_bh = -1, cur_qg = -1;
+  u32x4 qf[2][C::kSteps];
+  float nb[2][16];
+
+  while (s < e) {
+    // ---- locate the segment that starts at global tile s
+    int b = 0;
+    while (b + 1 < prm.B && map.toff[b + 1] <= s) ++b;
+    const int P = prm.lens.P[b];
+    const int npt = ceil_div(P, C::kTK);
+    const int nrt = ceil_div(prm.n_resp, C::kTK);
+    const int tiles_h = map.with_resp ? npt + nrt : npt;
+    const int rem = s - map.toff[b];
+    const int h = rem / tiles_h;
+    const int t_in = rem - h * tiles_h;
+    const bool prompt = t_in < npt;
+    const int head0 = map.toff[b] + h * tiles_h;
+    const int region_start = head0 + (prompt ? 0 : npt);
+    const int region_end = head0 + (prompt ? npt : tiles_h);
+    const int seg_end = min(e, region_end);
+    const int nt = seg_end - s;
+    const int k0 = (prompt ? 0 : P) + (s - region_start) * C::kTK;
+    const int k1 = min(prompt ? P : P + prm.n_resp, k0 + nt * C::kTK);
+    const int bh = b * prm.H + h;
+    const char* kbase = prm.K.row(b, h, 0);
+    const int64_t kstride = prm.K.stride_t;
+
+    for (int qg = 0; qg < prm.n_query; qg += kQPerGroup) {
+      const int q0 = qg + wave * kQPerWave;
+      if (bh != cur_bh || qg != cur_qg) {
+        cur_bh = bh;
+        cur_qg = qg;
+        // Query fragments stay in registers for as long as the walk stays in this head.  Rows past
+        // n_query re-read the last query: their statistics are never stored (pass 1) and their
+        // probabilities are forced to zero through nb = -inf (pass 2).
+        const char* qbase = prm.Q.row(b, h, 0);
 #pragma unroll
-    for (int blk = 0; blk < 2; ++blk) {
-      const int q = q0 + blk * 32 + r;
+        for (int blk = 0; blk < 2; ++blk) {
+          const int q = min(q0 + blk * 32 + r, prm.n_query - 1);
 #pragma unroll
-      for (int ks = 0; ks < C::kSteps; ++ks) {
-        if (q < prm.n_query)
-          qf[blk][ks] = *reinterpret_cast<const u32x4*>(prm.Q.row(b, h, q) + ks * 32 + g * 16);
-        else
-          qf[blk][ks] = u32x4{0u, 0u, 0u, 0u};
+          for (int ks = 0; ks < C::kSteps; ++ks)
+            qf[blk][ks] = *reinterpret_cast<const u32x4*>(qbase + (int64_t)q * prm.Q.stride_t + ks * 32 + g * 16);
+        }
+        if (PASS == 2) {
+          __syncthreads();
+          const int q = qg + (int)threadIdx.x;
+          nlse[threadIdx.x] = q < prm.n_query ? -prm.lse2[(int64_t)bh * prm.n_query + q] : -INFINITY;
+          __syncthreads();
+#pragma unroll
+          for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) nb[blk][i] = nlse[wave * kQPerWave + blk * 32 + 8 * (i / 4) + 4 * g + (i % 4)];
+        }
       }
-    }
 
-    // pass 1 state: this lane's running (max, sum) for query q0 + 32*blk + r over the keys it sees
-    float run_m[2] = {kNegBig, kNegBig};
-    float run_l[2] = {0.f, 0.f};
-    // pass 2 state: -lse2 of the 16 query rows this lane sees in each block
-    float nb[2][16];
-    if (PASS == 2) {
-#pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int q = q0 + blk * 32 + 8 * (i / 4) + 4 * g + (i % 4);
-          nb[blk][i] = (q < prm.n_query) ? -prm.lse2[(int64_t)bh * prm.n_query + q] : -INFINITY;
+      // pass 1 state: this lane's (reference exponent, sum) for query q0 + 32*blk + r over the keys it sees
+      float run_m[2] = {kNegBig, kNegBig};
+      float run_l[2] = {0.f, 0.f};
+
+      float* out = prm.scores + (int64_t)bh * prm.score_stride;
+      auto flush = [&](int t) {  // tile t of this segment: add the four waves' partials, write scores
+        const int j = k0 + t * C::kTK + (int)threadIdx.x;
+        if ((int)threadIdx.x < C::kTK && j < k1) {
+          const float v = cs[t & 1][0][threadIdx.x] + cs[t & 1][1][threadIdx.x] + cs[t & 1][2][threadIdx.x] +
+                          cs[t & 1][3][threadIdx.x];
+          out[j] = qg == 0 ? v : out[j] + v;
         }
-    }
+      };
 
-    u32x4 stage[C::kPieces];
-    __syncthreads();  // previous sweep's readers are done with the tile buffers
-    load_tile_global<T, D>(prm.K, b, h, k0, k1 - 1, stage);
-    store_tile_lds<T, D>(kt[0], stage);
-    __syncthreads();
+      u32x4 stage[C::kPieces];
+      __syncthreads();  // the previous segment's readers are done with the tile and partial buffers
+      load_tile_global<T, D>(kbase, kstride, k0, k1 - 1, stage);
+      store_tile_lds<T, D>(kt[0], stage);
+      __syncthreads();
 
-    for (int t = 0; t < ntiles; ++t) {
-      const int key0 = k0 + t * C::kTK;
-      if (t + 1 < ntiles) load_tile_global<T, D>(prm.K, b, h, key0 + C::kTK, k1 - 1, stage);
-      const char* buf = kt[t & 1];
+      for (int t = 0; t < nt; ++t) {
+        const int key0 = k0 + t * C::kTK;
+        if (t + 1 < nt) load_tile_global<T, D>(kbase, kstride, key0 + C::kTK, k1 - 1, stage);
+        if (PASS == 2 && t > 0) flush(t - 1);
+        const char* buf = kt[t & 1];
 
 #pragma unroll
-      for (int kb = 0; kb < C::kTK / 32; ++kb) {
-        f32x16 acc0 = {}, acc1 = {};
+        for (int kb = 0; kb < C::kTK / 32; ++kb) {
+          f32x16 acc0 = {}, acc1 = {};
 #pragma unroll
-        for (int ks = 0; ks < C::kSteps; ++ks) {
-          const u32x4 kf = *reinterpret_cast<const u32x4*>(buf + (kb * 32 + r) * C::kRowP + ks * 32 + g * 16);
-          if (PASS == 1) {  // S^T block: keys on rows, queries on columns
-            mfma_step<T>(kf, qf[0][ks], acc0);
-            mfma_step<T>(kf, qf[1][ks], acc1);
-          } else {          // S block: queries on rows, keys on columns
-            mfma_step<T>(qf[0][ks], kf, acc0);
-            mfma_step<T>(qf[1][ks], kf, acc1);
-          }
-        }
-        if (PASS == 1) {
-          const int nvalid = k1 - (key0 + kb * 32);  // rows >= nvalid of this block are past the chunk end
-          if (nvalid < 32) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const int row = 8 * (i / 4) + 4 * g + (i % 4);
-              if (row >= nvalid) {
-                acc0[i] = -INFINITY;
-                acc1[i] = -INFINITY;
-              }
+          for (int ks = 0; ks < C::kSteps; ++ks) {
+            const u32x4 kf = *reinterpret_cast<const u32x4*>(buf + (kb * 32 + r) * C::kRowP + ks * 32 + g * 16);
+            if (PASS == 1) {  // S^T block: keys on rows, queries on columns
+              mfma_step<T>(kf, qf[0][ks], acc0);
+              mfma_step<T>(kf, qf[1][ks], acc1);
+            } else {          // S block: queries on rows, keys on columns
+              mfma_step<T>(qf[0][ks], kf, acc0);
+              mfma_step<T>(qf[1][ks], kf, acc1);
             }
           }
+          if (PASS == 1) {
+            const int nvalid = k1 - (key0 + kb * 32);  // rows >= nvalid of this block are past the segment end
+            if (nvalid < 32) {
 #pragma unroll
-          for (int blk = 0; blk < 2; ++blk) {
-            const f32x16& a = blk ? acc1 : acc0;
-            float bm = a[0];
+              for (int i = 0; i < 16; ++i) {
+                const int row = 8 * (i / 4) + 4 * g + (i % 4);
+                if (row >= nvalid) {
+                  acc0[i] = -INFINITY;
+                  acc1[i] = -INFINITY;
+                }
+              }
+            }
 #pragma unroll
-            for (int i = 1; i < 16; ++i) bm = fmaxf(bm, a[i]);
-            const float m_new = fmaxf(run_m[blk], bm * c);
-            float s = 0.f;
+            for (int blk = 0; blk < 2; ++blk) {
+              const f32x16& a = blk ? acc1 : acc0;
+              // Exponentials against the current reference; the reference is only moved (slow path) when a
+              // sum leaves the safe range, which also covers the very first block (reference = -1e30).
+              float sum = 0.f;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) s += fast_exp2(fmaf(a[i], c, -m_new));
-            run_l[blk] = run_l[blk] * fast_exp2(run_m[blk] - m_new) + s;
-            run_m[blk] = m_new;
-          }
-        } else {
-          float cs = 0.f;
+              for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(a[i], c, -run_m[blk]));
+              if (__all(sum < kLazyLimit)) {
+                run_l[blk] += sum;
+              } else {
+                float bm = a[0];
 #pragma unroll
-          for (int i = 0; i < 16; ++i) cs += fast_exp2(fmaf(acc0[i], c, nb[0][i]));
+                for (int i = 1; i < 16; ++i) bm = fmaxf(bm, a[i]);
+                const float m_new = fmaxf(run_m[blk], bm * c);
+                sum = 0.f;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) cs += fast_exp2(fmaf(acc1[i], c, nb[1][i]));
-          cs += xor32(cs);
-          if (g == 0) {
-            float* dst = colsum + wave * prm.chunk + (key0 - k0) + kb * 32 + r;
-            *dst = (qg == 0) ? cs : (*dst + cs);
+                for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(a[i], c, -m_new));
+                run_l[blk] = run_l[blk] * fast_exp2(run_m[blk] - m_new) + sum;
+                run_m[blk] = m_new;
+              }
+            }
+          } else {
+            float colsum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) colsum += fast_exp2(fmaf(acc0[i], c, nb[0][i]));
+#pragma unroll
+            for (int i = 0; i < 16; ++i) colsum += fast_exp2(fmaf(acc1[i], c, nb[1][i]));
+            colsum += xor32(colsum);
+            if (g == 0) cs[t & 1][wave][kb * 32 + r] = colsum;
           }
         }
+
+        if (t + 1 < nt) store_tile_lds<T, D>(kt[(t + 1) & 1], stage);
+        __syncthreads();
       }
 
-      if (t + 1 < ntiles) store_tile_lds<T, D>(kt[(t + 1) & 1], stage);
-      __syncthreads();
-    }
-
-    if (PASS == 1) {
+      if (PASS == 1) {
+        const int part = (int)blockIdx.x - region_start / map.R;
+        const int slot = bh * (prm.parts_p + prm.parts_r) + (prompt ? 0 : prm.parts_p) + part;
 #pragma unroll
-      for (int blk = 0; blk < 2; ++blk) {
-        const float m_o = xor32(run_m[blk]);
-        const float l_o = xor32(run_l[blk]);
-        const float m = fmaxf(run_m[blk], m_o);
-        const float l = run_l[blk] * fast_exp2(run_m[blk] - m) + l_o * fast_exp2(m_o - m);
-        const int q = q0 + blk * 32 + r;
-        if (g == 0 && q < prm.n_query)
-          prm.stats[((int64_t)bh * prm.nch_max + blockIdx.x) * prm.n_query + q] = make_float2(m, l);
+        for (int blk = 0; blk < 2; ++blk) {
+          const float m_o = xor32(run_m[blk]);
+          const float l_o = xor32(run_l[blk]);
+          const float m = fmaxf(run_m[blk], m_o);
+          const float l = run_l[blk] * fast_exp2(run_m[blk] - m) + l_o * fast_exp2(m_o - m);
+          const int q = q0 + blk * 32 + r;
+          if (g == 0 && q < prm.n_query) prm.stats[(int64_t)slot * prm.n_query + q] = make_float2(m, l);
+        }
+      } else {
+        flush(nt - 1);
       }
     }
-  }
-
-  if (PASS == 2) {
-    // colsum was last written before the final barrier of the tile loop
-    float* out = prm.scores + (int64_t)bh * prm.score_stride + k0;
-    for (int j = threadIdx.x; j < k1 - k0; j += kScoreThreads) {
-      float s = 0.f;
-#pragma unroll
-      for (int w = 0; w < kScoreWaves; ++w) s += colsum[w * prm.chunk + j];
-      out[j] = s;
-    }
+    s = seg_end;
   }
 }
 
-// Merge the per-chunk statistics of every query row into its base-2 log-sum-exp; the prompt chunks'
+// Merge the per-segment statistics of every query row into its base-2 log-sum-exp; the prompt segments'
 // share of each row's normaliser, summed over the rows, is the mask-to-prompt attention mass.
 __global__ __launch_bounds__(256) void score_merge_kernel(const ScoreParams prm) {
   __shared__ float red[256];
+  const TileMap& map = prm.map1;
   const int bh = blockIdx.x;
   const int b = bh / prm.H;
+  const int h = bh % prm.H;
   const int P = prm.lens.P[b];
-  const int npc = (P + prm.chunk - 1) / prm.chunk;
-  const int nch = npc + (prm.n_resp + prm.chunk - 1) / prm.chunk;
+  const int npt = ceil_div(P, map.tk);
+  const int nrt = ceil_div(prm.n_resp, map.tk);
+  const int a_p = map.toff[b] + h * (npt + nrt);
+  const int a_r = a_p + npt;
+  const int np_parts = npt > 0 ? (a_p + npt - 1) / map.R - a_p / map.R + 1 : 0;
+  const int nr_parts = (a_r + nrt - 1) / map.R - a_r / map.R + 1;
+  const int nslot = prm.parts_p + prm.parts_r;
   float mass = 0.f;
   for (int q = threadIdx.x; q < prm.n_query; q += 256) {
-    const float2* st = prm.stats + (int64_t)bh * prm.nch_max * prm.n_query + q;
+    const float2* st = prm.stats + (int64_t)bh * nslot * prm.n_query + q;
     float M = kNegBig;
-    for (int ch = 0; ch < nch; ++ch) M = fmaxf(M, st[(int64_t)ch * prm.n_query].x);
-    float L = 0.f, Lp = 0.f;
-    for (int ch = 0; ch < nch; ++ch) {
-      const float2 v = st[(int64_t)ch * prm.n_query];
-      const float w = v.y * fast_exp2(v.x - M);
-      L += w;
-      if (ch < npc) Lp += w;
+    for (int i = 0; i < np_parts; ++i) M = fmaxf(M, st[(int64_t)i * prm.n_query].x);
+    for (int i = 0; i < nr_parts; ++i) M = fmaxf(M, st[(int64_t)(prm.parts_p + i) * prm.n_query].x);
+    float Lp = 0.f, Lr = 0.f;
+    for (int i = 0; i < np_parts; ++i) {
+      const float2 v = st[(int64_t)i * prm.n_query];
+      Lp += v.y * fast_exp2(v.x - M);
     }
+    for (int i = 0; i < nr_parts; ++i) {
+      const float2 v = st[(int64_t)(prm.parts_p + i) * prm.n_query];
+      Lr += v.y * fast_exp2(v.x - M);
+    }
+    const float L = Lp + Lr;
     prm.lse2[(int64_t)bh * prm.n_query + q] = M + __log2f(L);
     mass += Lp / L;
   }
@@ -274,14 +317,33 @@ __global__ __launch_bounds__(256) void score_merge_kernel(const ScoreParams prm)
   if (threadIdx.x == 0 && prm.prompt_mass) prm.prompt_mass[bh] = red[0];
 }
 
-int score_chunk_keys(const maskkv_desc* d) {
-  // Aim at roughly four workgroups per compute unit, chunks of 256..1024 keys.
-  const int64_t total = (int64_t)d->B * d->H * ((int64_t)d->P_max + d->n_resp);
-  int64_t c = (total + 1023) / 1024;
-  c = (c + 63) / 64 * 64;
-  if (c < 256) c = 256;
-  if (c > 1024) c = 1024;
-  return (int)c;
+int tile_keys(const maskkv_desc* d) { return d->d * (d->dtype == MASKKV_BF16 ? 2 : 4) <= 256 ? 64 : 32; }
+
+TileMap make_map(const maskkv_desc* d, const Lens& lens, bool with_resp) {
+  TileMap m;
+  m.tk = tile_keys(d);
+  m.with_resp = with_resp ? 1 : 0;
+  int t = 0;
+  for (int b = 0; b <= MASKKV_MAX_BATCH; ++b) m.toff[b] = 0;
+  for (int b = 0; b < d->B; ++b) {
+    m.toff[b] = t;
+    const int per_head = (lens.P[b] + m.tk - 1) / m.tk + (with_resp ? (d->n_resp + m.tk - 1) / m.tk : 0);
+    t += per_head * d->H;
+  }
+  for (int b = d->B; b <= MASKKV_MAX_BATCH; ++b) m.toff[b] = t;
+  m.T = t;
+  m.R = (t + kTargetGroups - 1) / kTargetGroups;
+  if (m.R < 1) m.R = 1;
+  return m;
+}
+
+// Partial-statistics slots per (b, h): a region of n tiles is touched by at most ceil(n/R)+1 workgroups.
+void stat_slots(const maskkv_desc* d, const Lens& lens, const TileMap& map1, int* parts_p, int* parts_r) {
+  int npt_max = 0;
+  for (int b = 0; b < d->B; ++b) npt_max = max(npt_max, (lens.P[b] + map1.tk - 1) / map1.tk);
+  const int nrt = (d->n_resp + map1.tk - 1) / map1.tk;
+  *parts_p = (npt_max + map1.R - 1) / map1.R + 1;
+  *parts_r = (nrt + map1.R - 1) / map1.R + 1;
 }
 
 int mark(void* const* events, int i, hipStream_t stream) {
@@ -293,22 +355,19 @@ int mark(void* const* events, int i, hipStream_t stream) {
 }
 
 template <typename T, int D>
-int launch_score_t(const ScoreParams& prm, int B, hipStream_t stream, void* const* events) {
+int launch_score_t(ScoreParams& prm, const TileMap& map2, hipStream_t stream, void* const* events) {
   const dim3 block(kScoreThreads);
-  const dim3 grid1(prm.nch_max, B * prm.H);
   if (int e = mark(events, 0, stream)) return e;
-  hipLaunchKernelGGL((score_kernel<T, D, 1>), grid1, block, 0, stream, prm);
+  prm.map = prm.map1;
+  hipLaunchKernelGGL((score_kernel<T, D, 1>), dim3((prm.map.T + prm.map.R - 1) / prm.map.R), block, 0, stream, prm);
   if (int e = check_launch("score pass 1")) return e;
   if (int e = mark(events, 1, stream)) return e;
-  hipLaunchKernelGGL(score_merge_kernel, dim3(B * prm.H), dim3(256), 0, stream, prm);
+  hipLaunchKernelGGL(score_merge_kernel, dim3(prm.B * prm.H), dim3(256), 0, stream, prm);
   if (int e = check_launch("score merge")) return e;
   if (int e = mark(events, 2, stream)) return e;
-  int npc_max = 0;
-  for (int b = 0; b < B; ++b) npc_max = max(npc_max, (prm.lens.P[b] + prm.chunk - 1) / prm.chunk);
-  if (npc_max > 0) {
-    const dim3 grid2(npc_max, B * prm.H);
-    const size_t dyn = sizeof(float) * kScoreWaves * prm.chunk;
-    hipLaunchKernelGGL((score_kernel<T, D, 2>), grid2, block, dyn, stream, prm);
+  if (map2.T > 0) {
+    prm.map = map2;
+    hipLaunchKernelGGL((score_kernel<T, D, 2>), dim3((map2.T + map2.R - 1) / map2.R), block, 0, stream, prm);
     if (int e = check_launch("score pass 2")) return e;
   }
   return mark(events, 3, stream);
@@ -316,11 +375,11 @@ int launch_score_t(const ScoreParams& prm, int B, hipStream_t stream, void* cons
 
 }  // namespace
 
-size_t score_workspace_bytes(const maskkv_desc* d) {
-  const int chunk = score_chunk_keys(d);
-  const int64_t nch = (d->P_max + chunk - 1) / chunk + (d->n_resp + chunk - 1) / chunk;
+size_t score_workspace_bytes(const maskkv_desc* d, const Lens& lens) {
+  int pp, pr;
+  stat_slots(d, lens, make_map(d, lens, true), &pp, &pr);
   const int64_t bh = (int64_t)d->B * d->H;
-  size_t stats = (size_t)(bh * nch * d->n_query) * sizeof(float2);
+  size_t stats = (size_t)(bh * (pp + pr) * d->n_query) * sizeof(float2);
   stats = (stats + 255) / 256 * 256;
   const size_t lse = (size_t)(bh * d->n_query) * sizeof(float);
   return stats + (lse + 255) / 256 * 256;
@@ -333,24 +392,27 @@ int launch_score(const maskkv_desc* d, const View& Q, const View& K, const Lens&
   prm.Q = Q;
   prm.K = K;
   prm.lens = lens;
+  prm.map1 = make_map(d, lens, true);
+  const TileMap map2 = make_map(d, lens, false);
+  prm.B = d->B;
   prm.H = d->H;
   prm.n_resp = d->n_resp;
   prm.n_query = d->n_query;
-  prm.chunk = score_chunk_keys(d);
-  prm.nch_max = (d->P_max + prm.chunk - 1) / prm.chunk + (d->n_resp + prm.chunk - 1) / prm.chunk;
+  stat_slots(d, lens, prm.map1, &prm.parts_p, &prm.parts_r);
   prm.c = scale * kLog2e;
   const int64_t bh = (int64_t)d->B * d->H;
-  size_t stats = (size_t)(bh * prm.nch_max * d->n_query) * sizeof(float2);
+  size_t stats = (size_t)(bh * (prm.parts_p + prm.parts_r) * d->n_query) * sizeof(float2);
   stats = (stats + 255) / 256 * 256;
   prm.stats = reinterpret_cast<float2*>(workspace);
   prm.lse2 = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + stats);
   prm.scores = scores;
   prm.score_stride = score_stride;
   prm.prompt_mass = prompt_mass;
-  if (d->dtype == MASKKV_BF16) {
-    return d->d == 128 ? launch_score_t<bf16_t, 128>(prm, d->B, stream, events) : launch_score_t<bf16_t, 64>(prm, d->B, stream, events);
-  }
-  return d->d == 128 ? launch_score_t<float, 128>(prm, d->B, stream, events) : launch_score_t<float, 64>(prm, d->B, stream, events);
+  if (d->dtype == MASKKV_BF16)
+    return d->d == 128 ? launch_score_t<bf16_t, 128>(prm, map2, stream, events)
+                       : launch_score_t<bf16_t, 64>(prm, map2, stream, events);
+  return d->d == 128 ? launch_score_t<float, 128>(prm, map2, stream, events)
+                     : launch_score_t<float, 64>(prm, map2, stream, events);
 }
 
 }  // namespace maskkv
