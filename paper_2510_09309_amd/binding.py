@@ -15,7 +15,8 @@ from typing import Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmaskkv.so")
+# MASKKV_LIB_PATH selects another build of the same library (e.g. an instrumented one)
+LIB_PATH = os.environ.get("MASKKV_LIB_PATH", os.path.join(_HERE, "libmaskkv.so"))
 
 MASKKV_F32, MASKKV_BF16 = 0, 1
 POOL_MEAN, POOL_MAX = 0, 1

@@ -3,10 +3,14 @@
 //
 // One workgroup of 16 waves serves one (b, h).  The pooled scores are turned into order-preserving
 // 32-bit keys and kept in LDS (or in a global scratch row when the prompt is longer than LDS holds).
-// The k-th largest key tau is found by an MSB-first radix select with 8-bit digits (LDS histogram,
-// wave-aggregated atomics when a wave's digits agree); the kept set is then "key > tau" plus the first
-// (k - count_gt) positions with key == tau, emitted in ascending position order with ballot/popcount
-// prefix sums, each wave walking one contiguous slice of the prompt.
+// The k-th largest key tau is found by range refinement: the current key range [lo, hi] (initially the
+// minimum and maximum key of the head) is cut into at most 2048 equal bins, an LDS histogram locates the
+// bin that holds the k-th largest key, and that bin becomes the new range.  Because the bins follow the
+// data's own range the histogram stays spread out (few colliding LDS atomics) for the narrow score
+// distributions attention produces, and three rounds always reach a single key.  After the first round
+// the candidates of the chosen bin are copied to a short LDS list, so later rounds touch only those.
+// The kept set is "key > tau" plus the first (k - count_gt) positions with key == tau, emitted in
+// ascending position order with ballot/popcount prefix sums, each wave walking one contiguous slice.
 #include "kernels.hpp"
 
 namespace maskkv {
@@ -15,7 +19,9 @@ namespace {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
-constexpr int kSelLdsCap = 36864;  // keys that fit the 160 KB LDS next to the small arrays (144 KB)
+constexpr int kSelLdsCap = 32768;  // keys kept in LDS (128 KB) next to the histogram and the candidate list
+constexpr int kBins = 2048;
+constexpr int kListCap = 2048;
 
 struct SelectParams {
   Lens lens;
@@ -44,14 +50,29 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
   return v;
 }
 
+// One histogram vote; lanes of a wave that all vote for the same bin are merged into one atomic.
+__device__ __forceinline__ void vote(int* hist, bool cand, uint32_t bin, int lane) {
+  const uint64_t cmask = __ballot(cand);
+  if (!cmask) return;
+  const int leader = __ffsll((unsigned long long)cmask) - 1;
+  const uint32_t b0 = __shfl(bin, leader, 64);
+  const uint64_t same = __ballot(cand && bin == b0);
+  if (same == cmask) {
+    if (lane == leader) atomicAdd(&hist[b0], __popcll(cmask));
+  } else if (cand) {
+    atomicAdd(&hist[bin], 1);
+  }
+}
+
 template <bool LDS_KEYS>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams prm) {
   extern __shared__ uint32_t lds_keys[];
-  __shared__ int hist[256];
+  __shared__ int hist[kBins];
+  __shared__ uint32_t list[kListCap];
   __shared__ int wsum[kSelWaves][2];
-  __shared__ uint32_t sh_prefix;
-  __shared__ int sh_krem;
-  __shared__ int sh_base;
+  __shared__ uint32_t wmin[kSelWaves], wmax[kSelWaves];
+  __shared__ uint32_t sh_lo, sh_hi;
+  __shared__ int sh_krem, sh_base, sh_nlist, sh_bincount;
 
   const int bh = blockIdx.x;
   const int b = bh / prm.H;
@@ -83,72 +104,152 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
   }
   if (k == 0) return;
 
-  // ---- pooled scores -> order-preserving keys
+  // ---- pooled scores -> order-preserving keys, and the key range of the head
   const float* x = prm.scores + (int64_t)bh * prm.score_stride;
   const int r = (prm.window - 1) / 2;
-  for (int j = tid; j < P; j += kSelThreads) {
-    const int lo = max(0, j - r);
-    const int hi = min(P - 1, j + r);
-    float v;
-    if (prm.mode == MASKKV_POOL_MAX) {
-      v = x[lo];
-      for (int t = lo + 1; t <= hi; ++t) v = fmaxf(v, x[t]);
-    } else {
-      v = x[lo];
-      for (int t = lo + 1; t <= hi; ++t) v = __fadd_rn(v, x[t]);
-      v = __fdiv_rn(v, (float)(hi - lo + 1));
-    }
-    keys[j] = order_key(v);
-  }
-  if (tid == 0) {
-    sh_prefix = 0u;
-    sh_krem = k;
-  }
-
-  // ---- radix select of the k-th largest key
-  for (int pass = 0; pass < 4; ++pass) {
-    const int shift = 24 - 8 * pass;
-    if (tid < 256) hist[tid] = 0;
-    __syncthreads();  // also orders the key writes (and the global scratch writes within the block)
-    const uint32_t prefix = sh_prefix;
-    const int krem = sh_krem;
-    const uint32_t himask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
-    for (int j0 = 0; j0 < P; j0 += kSelThreads) {
-      const int j = j0 + tid;
-      const bool cand = j < P && ((keys[j] & himask) == prefix);
-      const uint32_t digit = cand ? ((keys[j] >> shift) & 255u) : 0u;
-      const uint64_t cmask = __ballot(cand);
-      if (cmask) {
-        const int leader = __ffsll((unsigned long long)cmask) - 1;
-        const uint32_t d0 = __shfl(digit, leader, 64);
-        const uint64_t same = __ballot(cand && digit == d0);
-        if (same == cmask) {
-          if (lane == leader) atomicAdd(&hist[d0], __popcll(cmask));
-        } else if (cand) {
-          atomicAdd(&hist[digit], 1);
+  uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+  if (r <= 3 && prm.mode == MASKKV_POOL_MEAN) {
+    // four consecutive positions per thread: ten loads serve four windows of up to seven terms
+    for (int j0 = tid * 4; j0 < P; j0 += kSelThreads * 4) {
+      float v[10];
+#pragma unroll
+      for (int i = 0; i < 10; ++i) {
+        const int j = j0 - 3 + i;
+        v[i] = (j >= 0 && j < P) ? x[j] : 0.f;
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int j = j0 + e;
+        if (j < P) {
+          const int lo = max(0, j - r), hi = min(P - 1, j + r);
+          float acc = 0.f;
+          bool first = true;
+#pragma unroll
+          for (int t = -3; t <= 3; ++t) {
+            const int jj = j + t;
+            if (jj >= lo && jj <= hi) {  // in-range terms only, lowest index first
+              acc = first ? v[e + 3 + t] : __fadd_rn(acc, v[e + 3 + t]);
+              first = false;
+            }
+          }
+          const uint32_t key = order_key(__fdiv_rn(acc, (float)(hi - lo + 1)));
+          keys[j] = key;
+          kmin = min(kmin, key);
+          kmax = max(kmax, key);
         }
       }
     }
-    __syncthreads();
-    // suffix counts from the top bin; exactly one bin straddles the k-th largest
-    // (waves 0..3 hold the 256 bins, top bin first)
-    int val = 0, incl = 0;
-    if (tid < 256) {
-      val = hist[255 - tid];
-      incl = wave_incl_scan(val, lane);
-      if (lane == 63) wsum[wave][0] = incl;
+  } else {
+    for (int j = tid; j < P; j += kSelThreads) {
+      const int lo = max(0, j - r);
+      const int hi = min(P - 1, j + r);
+      float v = x[lo];
+      if (prm.mode == MASKKV_POOL_MAX) {
+        for (int t = lo + 1; t <= hi; ++t) v = fmaxf(v, x[t]);
+      } else {
+        for (int t = lo + 1; t <= hi; ++t) v = __fadd_rn(v, x[t]);
+        v = __fdiv_rn(v, (float)(hi - lo + 1));
+      }
+      const uint32_t key = order_key(v);
+      keys[j] = key;
+      kmin = min(kmin, key);
+      kmax = max(kmax, key);
     }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, 64));
+    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, 64));
+  }
+  if (lane == 0) {
+    wmin[wave] = kmin;
+    wmax[wave] = kmax;
+  }
+  __syncthreads();  // also orders the key writes (and the global scratch writes within the block)
+  if (tid == 0) {
+    uint32_t lo = wmin[0], hi = wmax[0];
+    for (int w = 1; w < kSelWaves; ++w) {
+      lo = min(lo, wmin[w]);
+      hi = max(hi, wmax[w]);
+    }
+    sh_lo = lo;
+    sh_hi = hi;
+    sh_krem = k;
+    sh_nlist = -1;  // no candidate list yet: rounds scan the whole head
+  }
+  __syncthreads();
+
+  // ---- range refinement until a single key remains
+  for (int round = 0; round < 4; ++round) {
+    const uint32_t lo = sh_lo, hi = sh_hi;
+    const int krem = sh_krem;
+    const int nlist = sh_nlist;
+    if (lo == hi) break;
+    const uint32_t width = hi - lo;
+    const int shift = max(0, 32 - __clz(width) - 11);  // (width >> shift) < 2048
+    const int nb = (int)(width >> shift) + 1;
+    for (int i = tid; i < nb; i += kSelThreads) hist[i] = 0;
     __syncthreads();
-    if (tid < 256) {
-      for (int w = 0; w < wave; ++w) incl += wsum[w][0];
-      if (incl >= krem && incl - val < krem) {
-        sh_prefix = prefix | ((uint32_t)(255 - tid) << shift);
-        sh_krem = krem - (incl - val);
+    if (nlist < 0) {
+      for (int j0 = 0; j0 < P; j0 += kSelThreads) {
+        const int j = j0 + tid;
+        const uint32_t key = j < P ? keys[j] : 0u;
+        const bool cand = j < P && key >= lo && key <= hi;
+        vote(hist, cand, cand ? ((key - lo) >> shift) : 0u, lane);
+      }
+    } else {
+      for (int j0 = 0; j0 < nlist; j0 += kSelThreads) {
+        const int j = j0 + tid;
+        const uint32_t key = j < nlist ? list[j] : 0u;
+        const bool cand = j < nlist && key >= lo && key <= hi;
+        vote(hist, cand, cand ? ((key - lo) >> shift) : 0u, lane);
       }
     }
     __syncthreads();
+    // Walk the bins from the top, two per thread; exactly one bin straddles the krem-th largest key.
+    {
+      const int b0 = nb - 1 - 2 * tid, b1 = nb - 2 - 2 * tid;
+      const int h0 = b0 >= 0 ? hist[b0] : 0;
+      const int h1 = b1 >= 0 ? hist[b1] : 0;
+      int incl = wave_incl_scan(h0 + h1, lane);
+      if (lane == 63) wsum[wave][0] = incl;
+      __syncthreads();
+      for (int w = 0; w < wave; ++w) incl += wsum[w][0];
+      const int before = incl - (h0 + h1);
+      if (incl >= krem && before < krem) {
+        const bool in0 = before + h0 >= krem;
+        const int bsel = in0 ? b0 : b1;
+        const int above = in0 ? before : before + h0;
+        const uint32_t nlo = lo + ((uint32_t)bsel << shift);
+        const uint32_t span = (shift == 0) ? 0u : ((1u << shift) - 1u);
+        sh_lo = nlo;
+        sh_hi = (uint32_t)min((uint64_t)hi, (uint64_t)nlo + span);
+        sh_krem = krem - above;
+        sh_bincount = in0 ? h0 : h1;
+      }
+      __syncthreads();
+    }
+    // First round: move the chosen bin's candidates to the short list if they fit.
+    if (nlist < 0 && sh_lo != sh_hi && sh_bincount <= kListCap) {
+      const uint32_t nlo = sh_lo, nhi = sh_hi;
+      if (tid == 0) sh_nlist = 0;
+      __syncthreads();
+      for (int j0 = 0; j0 < P; j0 += kSelThreads) {
+        const int j = j0 + tid;
+        const uint32_t key = j < P ? keys[j] : 0u;
+        const bool cand = j < P && key >= nlo && key <= nhi;
+        const uint64_t m = __ballot(cand);
+        if (m) {
+          int pos = 0;
+          if (lane == __ffsll((unsigned long long)m) - 1) pos = atomicAdd(&sh_nlist, __popcll(m));
+          pos = __shfl(pos, __ffsll((unsigned long long)m) - 1, 64);
+          if (cand) list[pos + __popcll(m & ((1ull << lane) - 1ull))] = key;
+        }
+      }
+      __syncthreads();
+    }
   }
-  const uint32_t tau = sh_prefix;
+  const uint32_t tau = sh_lo;
   const int need_eq = sh_krem;  // how many positions equal to tau are kept (lowest positions first)
 
   // ---- ordered emit: wave w owns positions [w*seg, (w+1)*seg)
