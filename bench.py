@@ -11,7 +11,7 @@ the device before the timed region.
 
 Prints ONE JSON line: the metric (prompt tokens scored+evicted per second per layer, whole step),
 per-call timings, compressed- and full-cache attention TFLOP/s, a roofline object for the dominant
-kernel (score pass 2, timed with HIP events on the launch stream inside the timed region) and the
+kernel (score pass 1, timed with HIP events on the launch stream inside the timed region) and the
 CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
@@ -31,6 +31,8 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
+# measured with rocprofv3 --pmc (profiles/score_pass1_c4_hbm_traffic.md): read + written bytes per launch
+SCORE_PASS1_TRAFFIC_BYTES = {"C4": 141296.5 * 1024 * 2.0 + 1124.0 * 1024}
 
 WORKLOADS = {
     # name: (H, d, P, n_m, avg budget, planted, layers resident)
@@ -130,6 +132,9 @@ def main():
     ap.add_argument("--workload", default="C4", choices=sorted(WORKLOADS))
     ap.add_argument("--resident-layers", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="before the warm-up, copy 256 MiB device-to-device three times: a kernel of known traffic "
+                         "against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures the hot path on ONE GPU; --gpus must be 1 "
@@ -178,20 +183,27 @@ def main():
         mk.maskkv_compact(desc, K, V, idx, cu, cap, Kc, Vc, stream)
         mk.maskkv_attend(desc, Q, Kc, Vc, cu, cap, Kr, Vr, 0.0, O, None, ws_att, stream)
 
+    if args.calibration_copy:
+        src = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
 
-    # ---- the timed region: exactly --steps whole-path steps; score pass 2 is bracketed by HIP events
+    # ---- the timed region: exactly --steps whole-path steps; score pass 1 is bracketed by HIP events
     ev = [(hev.create(), hev.create()) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(i, (0, 0, ev[i][0], ev[i][1]))
+        step(i, (ev[i][0], ev[i][1], 0, 0))
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    pass2_ms = float(np.mean([hev.elapsed_ms(a, b) for a, b in ev]))
+    pass1_ms = float(np.mean([hev.elapsed_ms(a, b) for a, b in ev]))
     for a, b in ev:
         hev.destroy(a)
         hev.destroy(b)
@@ -242,7 +254,7 @@ def main():
                                f"one layer per step, {len(layers)} resident layers rotated",
                    "global_batch": 1, "seq_len": N},
         "breakdown_ms": {"score": t_score, "select": t_select, "compact": t_compact, "attend": t_attend,
-                         "attend_full": t_full, "score_pass2_in_timed_region": pass2_ms},
+                         "attend_full": t_full, "score_pass1_in_timed_region": pass1_ms},
         "tokens_scored_evicted_per_s": P / ((t_score + t_select + t_compact) * 1e-3),
         "attend_compressed_tflops": flop_attend / (t_attend * 1e-3) / 1e12,
         "attend_full_tflops": flop_full / (t_full * 1e-3) / 1e12,
@@ -251,10 +263,13 @@ def main():
         "score_k_read_gbs_algorithmic": bytes_k / (t_score * 1e-3) / 1e9,
         "gather_gbs": bytes_gather / (t_compact * 1e-3) / 1e9,
         "roofline": {
-            "kernel": "score_kernel<bf16,128,pass 2> (QK^T over the prompt keys + exp + column sums)",
-            "bound": "mfma", "achieved": flop_qk_prompt / (pass2_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
-            "unit": "TFLOP/s", "frac": flop_qk_prompt / (pass2_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-            "traffic": None,
+            "kernel": "score_kernel<bf16,128,pass 1> (QK^T over all keys + exp + row statistics)",
+            "bound": "mfma", "achieved": flop_qk_all / (pass1_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": flop_qk_all / (pass1_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            # HBM bytes per launch from rocprofv3 FETCH_SIZE (x2.0 calibration) + WRITE_SIZE (x1.0), C4 only
+            "traffic": SCORE_PASS1_TRAFFIC_BYTES.get(args.workload),
+            "hbm_view": {"achieved_GBs": (bytes_k + 2.0 * n_m * d * H) / (pass1_ms * 1e-3) / 1e9,
+                         "peak_GBs": HBM_PEAK_GBS},
         },
     }
     if not args.no_cpu_baseline:
