@@ -12,6 +12,8 @@ FLAGS = [
     "-shared", "-fPIC", "-O3", "-std=c++17", "--offload-arch=gfx950",
     # packed fp32 arithmetic is kept off for every kernel in this library
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # MFMA accumulators in ordinary VGPRs: the exponentials read them directly (no v_accvgpr_read copies)
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
 ]
 
 
