@@ -17,6 +17,8 @@
 // stream through a padded, double-buffered LDS tile shared by the four waves.  Pass 1 puts keys on the
 // MFMA row axis so that a lane owns one query and the softmax statistics never leave the lane; pass 2
 // puts queries on the row axis so that the sum over queries is in-lane adds plus one cross-lane exchange.
+#include <type_traits>
+
 #include "kernels.hpp"
 
 namespace maskkv {
@@ -35,9 +37,11 @@ struct ScoreCfg {
   static constexpr int kRowB = D * (int)sizeof(T);     // bytes per K row
   static constexpr int kRowP = kRowB + 16;             // padded LDS row: conflict-free 16-byte reads
   static constexpr int kSteps = kRowB / 32;            // fragments per row
-  static constexpr int kTK = (kRowB <= 256) ? 64 : 32; // keys per tile
+  static constexpr int kTK = 64;                       // keys per tile: two 32-key blocks
   static constexpr int kPieces = kTK * kRowB / 16 / kScoreThreads;  // 16-byte pieces per thread per tile
   static constexpr int kPiecesPerRow = kRowB / 16;
+  static constexpr int kTileBytes = kTK * kRowP;
+  static constexpr int kLdsBytes = 2 * kTileBytes;     // double-buffered K tile (dynamic LDS)
 };
 
 // Tile bookkeeping of one pass, computed on the host.
@@ -94,10 +98,10 @@ __device__ __forceinline__ void store_tile_lds(char* buf, const u32x4 (&regs)[Sc
 
 // PASS 1: row statistics.  PASS 2: column sums.
 template <typename T, int D, int PASS>
-__global__ __launch_bounds__(kScoreThreads) void score_kernel(const ScoreParams prm) {
+__global__ __launch_bounds__(kScoreThreads, 2) void score_kernel(const ScoreParams prm) {
   using C = ScoreCfg<T, D>;
-  __shared__ __attribute__((aligned(16))) char kt[2][C::kTK * C::kRowP];
-  __shared__ float cs[2][kScoreWaves][C::kTK];  // pass 2: per-wave column partials of the last two tiles
+  extern __shared__ __attribute__((aligned(16))) char kt_raw[];  // two K tiles
+  __shared__ float cs[3][kScoreWaves][C::kTK];  // pass 2: per-wave column partials of the last three tiles
   __shared__ float nlse[kQPerGroup];            // pass 2: -lse2 of the current query group
 
   const int lane = threadIdx.x & 63;
@@ -172,85 +176,113 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const ScoreParams 
       auto flush = [&](int t) {  // tile t of this segment: add the four waves' partials, write scores
         const int j = k0 + t * C::kTK + (int)threadIdx.x;
         if ((int)threadIdx.x < C::kTK && j < k1) {
-          const float v = cs[t & 1][0][threadIdx.x] + cs[t & 1][1][threadIdx.x] + cs[t & 1][2][threadIdx.x] +
-                          cs[t & 1][3][threadIdx.x];
+          const float v = cs[t % 3][0][threadIdx.x] + cs[t % 3][1][threadIdx.x] + cs[t % 3][2][threadIdx.x] +
+                          cs[t % 3][3][threadIdx.x];
           out[j] = qg == 0 ? v : out[j] + v;
         }
       };
 
-      u32x4 stage[C::kPieces];
-      __syncthreads();  // the previous segment's readers are done with the tile and partial buffers
-      load_tile_global<T, D>(kbase, kstride, k0, k1 - 1, stage);
-      store_tile_lds<T, D>(kt[0], stage);
-      __syncthreads();
-
-      for (int t = 0; t < nt; ++t) {
-        const int key0 = k0 + t * C::kTK;
-        if (t + 1 < nt) load_tile_global<T, D>(kbase, kstride, key0 + C::kTK, k1 - 1, stage);
-        if (PASS == 2 && t > 0) flush(t - 1);
-        const char* buf = kt[t & 1];
-
+      // Logits of one 32-key block (both 32-query blocks of this wave) on the matrix pipe.
+      auto form = [&](const char* buf, int kb, f32x16& a0, f32x16& a1) {
+        a0 = f32x16{};
+        a1 = f32x16{};
 #pragma unroll
-        for (int kb = 0; kb < C::kTK / 32; ++kb) {
-          f32x16 acc0 = {}, acc1 = {};
-#pragma unroll
-          for (int ks = 0; ks < C::kSteps; ++ks) {
-            const u32x4 kf = *reinterpret_cast<const u32x4*>(buf + (kb * 32 + r) * C::kRowP + ks * 32 + g * 16);
-            if (PASS == 1) {  // S^T block: keys on rows, queries on columns
-              mfma_step<T>(kf, qf[0][ks], acc0);
-              mfma_step<T>(kf, qf[1][ks], acc1);
-            } else {          // S block: queries on rows, keys on columns
-              mfma_step<T>(qf[0][ks], kf, acc0);
-              mfma_step<T>(qf[1][ks], kf, acc1);
-            }
-          }
-          if (PASS == 1) {
-            const int nvalid = k1 - (key0 + kb * 32);  // rows >= nvalid of this block are past the segment end
-            if (nvalid < 32) {
-#pragma unroll
-              for (int i = 0; i < 16; ++i) {
-                const int row = 8 * (i / 4) + 4 * g + (i % 4);
-                if (row >= nvalid) {
-                  acc0[i] = -INFINITY;
-                  acc1[i] = -INFINITY;
-                }
-              }
-            }
-#pragma unroll
-            for (int blk = 0; blk < 2; ++blk) {
-              const f32x16& a = blk ? acc1 : acc0;
-              // Exponentials against the current reference; the reference is only moved (slow path) when a
-              // sum leaves the safe range, which also covers the very first block (reference = -1e30).
-              float sum = 0.f;
-#pragma unroll
-              for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(a[i], c, -run_m[blk]));
-              if (__all(sum < kLazyLimit)) {
-                run_l[blk] += sum;
-              } else {
-                float bm = a[0];
-#pragma unroll
-                for (int i = 1; i < 16; ++i) bm = fmaxf(bm, a[i]);
-                const float m_new = fmaxf(run_m[blk], bm * c);
-                sum = 0.f;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(a[i], c, -m_new));
-                run_l[blk] = run_l[blk] * fast_exp2(run_m[blk] - m_new) + sum;
-                run_m[blk] = m_new;
-              }
-            }
-          } else {
-            float colsum = 0.f;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) colsum += fast_exp2(fmaf(acc0[i], c, nb[0][i]));
-#pragma unroll
-            for (int i = 0; i < 16; ++i) colsum += fast_exp2(fmaf(acc1[i], c, nb[1][i]));
-            colsum += xor32(colsum);
-            if (g == 0) cs[t & 1][wave][kb * 32 + r] = colsum;
+        for (int ks = 0; ks < C::kSteps; ++ks) {
+          const u32x4 kf = *reinterpret_cast<const u32x4*>(buf + (kb * 32 + r) * C::kRowP + ks * 32 + g * 16);
+          if (PASS == 1) {  // S^T block: keys on rows, queries on columns
+            mfma_step<T>(kf, qf[0][ks], a0);
+            mfma_step<T>(kf, qf[1][ks], a1);
+          } else {          // S block: queries on rows, keys on columns
+            mfma_step<T>(qf[0][ks], kf, a0);
+            mfma_step<T>(qf[1][ks], kf, a1);
           }
         }
+      };
+      // Exponentials and sums of one formed block on the vector pipe.  MASKED is only needed for the last
+      // tile of a segment (rows past the segment end re-read its last row and must not be counted).
+      auto reduce = [&](auto masked, int t, int kb, f32x16& a0, f32x16& a1) {
+        if (PASS == 1) {
+          if (decltype(masked)::value) {
+            const int nvalid = k1 - (k0 + t * C::kTK + kb * 32);  // rows >= nvalid are past the segment end
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int row = 8 * (i / 4) + 4 * g + (i % 4);
+              if (row >= nvalid) {
+                a0[i] = -INFINITY;
+                a1[i] = -INFINITY;
+              }
+            }
+          }
+          // Exponentials against the current reference; the reference is only moved (slow path) when a sum
+          // leaves the safe range, which also covers the very first block (reference = -1e30).  One
+          // branch per block pair, after all the vector work, keeps the fast path a single basic block.
+          float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) s0 += fast_exp2(fmaf(a0[i], c, -run_m[0]));
+#pragma unroll
+          for (int i = 0; i < 16; ++i) s1 += fast_exp2(fmaf(a1[i], c, -run_m[1]));
+          if (__all(s0 < kLazyLimit && s1 < kLazyLimit)) {
+            run_l[0] += s0;
+            run_l[1] += s1;
+          } else {
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk) {
+              const f32x16& a = blk ? a1 : a0;
+              float bm = a[0];
+#pragma unroll
+              for (int i = 1; i < 16; ++i) bm = fmaxf(bm, a[i]);
+              const float m_new = fmaxf(run_m[blk], bm * c);
+              float sum = 0.f;
+#pragma unroll
+              for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(a[i], c, -m_new));
+              run_l[blk] = run_l[blk] * fast_exp2(run_m[blk] - m_new) + sum;
+              run_m[blk] = m_new;
+            }
+          }
+        } else {
+          float colsum = 0.f;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) colsum += fast_exp2(fmaf(a0[i], c, nb[0][i]));
+#pragma unroll
+          for (int i = 0; i < 16; ++i) colsum += fast_exp2(fmaf(a1[i], c, nb[1][i]));
+          colsum += xor32(colsum);
+          if (g == 0) cs[t % 3][wave][kb * 32 + r] = colsum;
+        }
+      };
 
-        if (t + 1 < nt) store_tile_lds<T, D>(kt[(t + 1) & 1], stage);
+      // Software pipeline inside every wave: while the matrix pipe forms block n+1 into one accumulator
+      // pair, the vector pipe reduces block n from the other pair (both in one basic block, so that the
+      // compiler interleaves MFMA and VALU issue).  A tile holds blocks (t,0) and (t,1):
+      //   stage 1 of iteration t: form (t,1) -> B  |  reduce (t,0) from A
+      //   tile t+1: registers -> LDS, barrier, request tile t+2 from global memory
+      //   stage 2 of iteration t: form (t+1,0) -> A  |  reduce (t,1) from B
+      u32x4 stage[C::kPieces];
+      f32x16 accA0, accA1, accB0, accB1;
+      __syncthreads();  // the previous segment's readers are done with the tile and partial buffers
+      load_tile_global<T, D>(kbase, kstride, k0, k1 - 1, stage);
+      store_tile_lds<T, D>(kt_raw, stage);
+      if (nt > 1) load_tile_global<T, D>(kbase, kstride, k0 + C::kTK, k1 - 1, stage);
+      __syncthreads();
+      form(kt_raw, 0, accA0, accA1);
+
+      auto iteration = [&](auto masked, int t) {
+        form(kt_raw + (t & 1) * C::kTileBytes, 1, accB0, accB1);
+        reduce(masked, t, 0, accA0, accA1);
+        if (t + 1 < nt) store_tile_lds<T, D>(kt_raw + ((t + 1) & 1) * C::kTileBytes, stage);
+        __syncthreads();  // tile t+1 is visible; every wave is done reading tile t-1 and reducing into cs[(t-1)%3]
+        if (t + 2 < nt) load_tile_global<T, D>(kbase, kstride, k0 + (t + 2) * C::kTK, k1 - 1, stage);
+        if (PASS == 2 && t > 0) flush(t - 1);
+        if (t + 1 < nt) form(kt_raw + ((t + 1) & 1) * C::kTileBytes, 0, accA0, accA1);
+        reduce(masked, t, 1, accB0, accB1);
+      };
+      for (int t = 0; t + 1 < nt; ++t) iteration(std::false_type{}, t);
+      if (PASS == 1 && k1 - k0 < nt * C::kTK)
+        iteration(std::true_type{}, nt - 1);  // partial last tile
+      else
+        iteration(std::false_type{}, nt - 1);
+      if (PASS == 2) {
         __syncthreads();
+        flush(nt - 1);
       }
 
       if (PASS == 1) {
@@ -265,8 +297,6 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const ScoreParams 
           const int q = q0 + blk * 32 + r;
           if (g == 0 && q < prm.n_query) prm.stats[(int64_t)slot * prm.n_query + q] = make_float2(m, l);
         }
-      } else {
-        flush(nt - 1);
       }
     }
     s = seg_end;
@@ -317,7 +347,7 @@ __global__ __launch_bounds__(256) void score_merge_kernel(const ScoreParams prm)
   if (threadIdx.x == 0 && prm.prompt_mass) prm.prompt_mass[bh] = red[0];
 }
 
-int tile_keys(const maskkv_desc* d) { return d->d * (d->dtype == MASKKV_BF16 ? 2 : 4) <= 256 ? 64 : 32; }
+int tile_keys(const maskkv_desc*) { return 64; }  // every configuration uses 64-key tiles
 
 TileMap make_map(const maskkv_desc* d, const Lens& lens, bool with_resp) {
   TileMap m;
@@ -354,21 +384,37 @@ int mark(void* const* events, int i, hipStream_t stream) {
   return MASKKV_EHIP;
 }
 
+template <typename T, int D, int PASS>
+int launch_pass(const ScoreParams& prm, hipStream_t stream) {
+  using C = ScoreCfg<T, D>;
+  static bool raised = false;  // one-time opt-in to more than the default dynamic LDS size
+  if (C::kLdsBytes > 48 * 1024 && !raised) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<T, D, PASS>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
+    if (e != hipSuccess) {
+      set_error("score: cannot raise dynamic LDS limit: %s", hipGetErrorString(e));
+      (void)hipGetLastError();
+      return MASKKV_EHIP;
+    }
+    raised = true;
+  }
+  const dim3 grid((prm.map.T + prm.map.R - 1) / prm.map.R);
+  hipLaunchKernelGGL((score_kernel<T, D, PASS>), grid, dim3(kScoreThreads), C::kLdsBytes, stream, prm);
+  return check_launch(PASS == 1 ? "score pass 1" : "score pass 2");
+}
+
 template <typename T, int D>
 int launch_score_t(ScoreParams& prm, const TileMap& map2, hipStream_t stream, void* const* events) {
-  const dim3 block(kScoreThreads);
   if (int e = mark(events, 0, stream)) return e;
   prm.map = prm.map1;
-  hipLaunchKernelGGL((score_kernel<T, D, 1>), dim3((prm.map.T + prm.map.R - 1) / prm.map.R), block, 0, stream, prm);
-  if (int e = check_launch("score pass 1")) return e;
+  if (int e = launch_pass<T, D, 1>(prm, stream)) return e;
   if (int e = mark(events, 1, stream)) return e;
   hipLaunchKernelGGL(score_merge_kernel, dim3(prm.B * prm.H), dim3(256), 0, stream, prm);
   if (int e = check_launch("score merge")) return e;
   if (int e = mark(events, 2, stream)) return e;
   if (map2.T > 0) {
     prm.map = map2;
-    hipLaunchKernelGGL((score_kernel<T, D, 2>), dim3((map2.T + map2.R - 1) / map2.R), block, 0, stream, prm);
-    if (int e = check_launch("score pass 2")) return e;
+    if (int e = launch_pass<T, D, 2>(prm, stream)) return e;
   }
   return mark(events, 3, stream);
 }
