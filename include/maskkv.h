@@ -63,7 +63,8 @@ typedef enum maskkv_pool_mode { MASKKV_POOL_MEAN = 0, MASKKV_POOL_MAX = 1 } mask
  * A 4-D view [B, H, T, d] of Q, K, V or O in DEVICE memory.  Element (b, h, t, e) lives at
  *   ptr + ((b*stride_b + h*stride_h + (seq_start[b] + t)*stride_t + e) * sizeof(element)),
  * strides in elements, the head_dim axis contiguous.  Rows must be 16-byte aligned
- * (ptr and all strides multiples of 16 bytes).  [B,H,T,d], [B,T,H,d] and packed
+ * (ptr and all strides multiples of 16 bytes) and stride_t may not exceed 16 MiB in bytes
+ * (MASKKV_EINVAL otherwise).  [B,H,T,d], [B,T,H,d] and packed
  * variable-length [T_total,H,d] (stride_b = 0 with seq_start) are all expressible.
  */
 typedef struct maskkv_tensor {

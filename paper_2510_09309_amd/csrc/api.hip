@@ -81,6 +81,10 @@ int make_view(const maskkv_desc* d, const maskkv_tensor* t, const char* name, Vi
               (long long)t->stride_h, (long long)t->stride_t, d->d);
     return MASKKV_EINVAL;
   }
+  if (t->stride_t * eb > (int64_t)1 << 24) {  // kernels keep row offsets inside a 64-row tile in 32 bits
+    set_error("%s: token stride of %lld bytes exceeds the supported 16 MiB", name, (long long)(t->stride_t * eb));
+    return MASKKV_EINVAL;
+  }
   if (((uintptr_t)t->ptr & 15) || ((t->stride_b * eb) & 15) || ((t->stride_h * eb) & 15) || ((t->stride_t * eb) & 15)) {
     set_error("%s: pointer and strides must be multiples of 16 bytes", name);
     return MASKKV_EINVAL;

@@ -115,7 +115,7 @@ __global__ __launch_bounds__(kScoreThreads, 2) void score_kernel(const ScorePara
   const int e = min(map.T, s + map.R);
   int cur_bh = -1, cur_qg = -1;
   u32x4 qf[2][C::kSteps];
-  float nb[2][16];
+  f32x16 nb[2];  // pass 2: -lse2 / c of this lane's query rows, the initial value of every logits block
 
   while (s < e) {
     // ---- locate the segment that starts at global tile s
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(kScoreThreads, 2) void score_kernel(const ScorePara
 #pragma unroll
           for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) nb[blk][i] = nlse[wave * kQPerWave + blk * 32 + 8 * (i / 4) + 4 * g + (i % 4)];
+            for (int i = 0; i < 16; ++i) nb[blk][i] = nlse[wave * kQPerWave + blk * 32 + 8 * (i / 4) + 4 * g + (i % 4)] / c;
         }
       }
 
@@ -184,8 +184,10 @@ __global__ __launch_bounds__(kScoreThreads, 2) void score_kernel(const ScorePara
 
       // Logits of one 32-key block (both 32-query blocks of this wave) on the matrix pipe.
       auto form = [&](const char* buf, int kb, f32x16& a0, f32x16& a1) {
-        a0 = f32x16{};
-        a1 = f32x16{};
+        // Pass 2 starts every block from -lse/c of its query rows: the matrix pipe then delivers s - lse/c
+        // and the vector pipe is left with one multiply, one exponential and one add per logit.
+        a0 = PASS == 2 ? nb[0] : f32x16{};
+        a1 = PASS == 2 ? nb[1] : f32x16{};
 #pragma unroll
         for (int ks = 0; ks < C::kSteps; ++ks) {
           const u32x4 kf = *reinterpret_cast<const u32x4*>(buf + (kb * 32 + r) * C::kRowP + ks * 32 + g * 16);
@@ -242,9 +244,9 @@ __global__ __launch_bounds__(kScoreThreads, 2) void score_kernel(const ScorePara
         } else {
           float colsum = 0.f;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) colsum += fast_exp2(fmaf(a0[i], c, nb[0][i]));
+          for (int i = 0; i < 16; ++i) colsum += fast_exp2(a0[i] * c);
 #pragma unroll
-          for (int i = 0; i < 16; ++i) colsum += fast_exp2(fmaf(a1[i], c, nb[1][i]));
+          for (int i = 0; i < 16; ++i) colsum += fast_exp2(a1[i] * c);
           colsum += xor32(colsum);
           if (g == 0) cs[t % 3][wave][kb * 32 + r] = colsum;
         }
