@@ -324,18 +324,29 @@ __global__ __launch_bounds__(256) void score_merge_kernel(const ScoreParams prm)
   float mass = 0.f;
   for (int q = threadIdx.x; q < prm.n_query; q += 256) {
     const float2* st = prm.stats + (int64_t)bh * nslot * prm.n_query + q;
-    float M = kNegBig;
-    for (int i = 0; i < np_parts; ++i) M = fmaxf(M, st[(int64_t)i * prm.n_query].x);
-    for (int i = 0; i < nr_parts; ++i) M = fmaxf(M, st[(int64_t)(prm.parts_p + i) * prm.n_query].x);
-    float Lp = 0.f, Lr = 0.f;
-    for (int i = 0; i < np_parts; ++i) {
-      const float2 v = st[(int64_t)i * prm.n_query];
-      Lp += v.y * fast_exp2(v.x - M);
-    }
-    for (int i = 0; i < nr_parts; ++i) {
-      const float2 v = st[(int64_t)(prm.parts_p + i) * prm.n_query];
-      Lr += v.y * fast_exp2(v.x - M);
-    }
+    // One sweep over the slots, eight independent loads at a time; (M, Lp, Lr) are rescaled on the fly.
+    float M = kNegBig, Lp = 0.f, Lr = 0.f;
+    auto sweep = [&](int first, int count, float& L) {
+      for (int i0 = 0; i0 < count; i0 += 8) {
+        float2 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          v[u] = i0 + u < count ? st[(int64_t)(first + i0 + u) * prm.n_query] : make_float2(kNegBig, 0.f);
+        float m8 = v[0].x;
+#pragma unroll
+        for (int u = 1; u < 8; ++u) m8 = fmaxf(m8, v[u].x);
+        if (m8 > M) {
+          const float f = fast_exp2(M - m8);
+          Lp *= f;
+          Lr *= f;
+          M = m8;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) L += v[u].y * fast_exp2(v[u].x - M);
+      }
+    };
+    sweep(0, np_parts, Lp);
+    sweep(prm.parts_p, nr_parts, Lr);
     const float L = Lp + Lr;
     prm.lse2[(int64_t)bh * prm.n_query + q] = M + __log2f(L);
     mass += Lp / L;
