@@ -105,8 +105,9 @@ __device__ __forceinline__ void store_kv(char* kt, char* vt, const u32x4 (&kr)[A
       for (int w = 0; w < 4; ++w) {
         const uint32_t lo = (a[w] & 0xFFFFu) | (bq[w] << 16);
         const uint32_t hi = (a[w] >> 16) | (bq[w] & 0xFFFF0000u);
-        vt32[(col * 8 + 2 * w) * (C::kSV / 2) + pair] = lo;
-        vt32[(col * 8 + 2 * w + 1) * (C::kSV / 2) + pair] = hi;
+        const int row = col * 8 + 2 * w;
+        vt32[row * (C::kSV / 2) + pair] = lo;
+        vt32[(row + 1) * (C::kSV / 2) + pair] = hi;
       }
     }
   } else {
@@ -170,15 +171,18 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const AttendParams 
   float m = kNegBig, l = 0.f;
   const float c = prm.c;
 
-  u32x4 kr[C::kPieces], vr[C::kPieces];
-  if (ntiles > 0) load_kv<T, D>(prm, ks, b, h, j0, j1 - 1, kr, vr);
+  // Two tiles are kept in flight in two register sets (a key axis of a few hundred rows is a short serial
+  // chain of tiles, so the memory latency of each request has to hide behind two tiles of arithmetic).
+  u32x4 kra[C::kPieces], vra[C::kPieces], krb[C::kPieces], vrb[C::kPieces];
+  if (ntiles > 0) load_kv<T, D>(prm, ks, b, h, j0, j1 - 1, kra, vra);
+  if (ntiles > 1) load_kv<T, D>(prm, ks, b, h, j0 + C::kTK, j1 - 1, krb, vrb);
 
-  for (int t = 0; t < ntiles; ++t) {
+  auto tile_step = [&](int t, u32x4 (&kr)[C::kPieces], u32x4 (&vr)[C::kPieces]) {
     const int key0 = j0 + t * C::kTK;
     __syncthreads();  // the previous tile's readers are done
     store_kv<T, D>(kt, vt, kr, vr);
     __syncthreads();
-    if (t + 1 < ntiles) load_kv<T, D>(prm, ks, b, h, key0 + C::kTK, j1 - 1, kr, vr);
+    if (t + 2 < ntiles) load_kv<T, D>(prm, ks, b, h, key0 + 2 * C::kTK, j1 - 1, kr, vr);
 
     // S^T = K Q^T for this tile
     f32x16 s[C::kNKB];
@@ -231,7 +235,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const AttendParams 
           u32x4 pf;
 #pragma unroll
           for (int w = 0; w < 4; ++w)
-            pf[w] = f32_to_bf16_rne(s[kb][8 * tp + 2 * w]) | (f32_to_bf16_rne(s[kb][8 * tp + 2 * w + 1]) << 16);
+            pf[w] = pack_bf16x2(s[kb][8 * tp + 2 * w], s[kb][8 * tp + 2 * w + 1]);
 #pragma unroll
           for (int db = 0; db < C::kDB; ++db) {
             const char* rowp = vt + ((db * 32 + r) * C::kSV + kb * 32 + 16 * tp + 4 * g) * 2;
@@ -260,6 +264,10 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const AttendParams 
           }
         }
     }
+  };
+  for (int t = 0; t < ntiles; t += 2) {
+    tile_step(t, kra, vra);
+    if (t + 1 < ntiles) tile_step(t + 1, krb, vrb);
   }
 
   const float l_tot = l + xor32(l);
@@ -276,8 +284,8 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const AttendParams 
         const float v2 = o[db][4 * qd + 2] * inv, v3 = o[db][4 * qd + 3] * inv;
         if (sizeof(T) == 2) {
           u32x2 w;
-          w[0] = f32_to_bf16_rne(v0) | (f32_to_bf16_rne(v1) << 16);
-          w[1] = f32_to_bf16_rne(v2) | (f32_to_bf16_rne(v3) << 16);
+          w[0] = pack_bf16x2(v0, v1);
+          w[1] = pack_bf16x2(v2, v3);
           *reinterpret_cast<u32x2*>(orow + e * 2) = w;
         } else {
           *reinterpret_cast<float4*>(orow + e * 4) = make_float4(v0, v1, v2, v3);
