@@ -127,7 +127,8 @@ int maskkv_score_profiled(const maskkv_desc* desc, const maskkv_tensor* Q_mask, 
                           float scale, float* scores, int64_t score_stride, float* prompt_mass,
                           void* workspace, size_t workspace_bytes, void* stream, void* const* events);
 
-/* Workspace (DEVICE bytes) needed by maskkv_select (may be 0). 256-byte alignment. */
+/* Workspace (DEVICE bytes) needed by maskkv_select: the candidates that its first stage (one workgroup
+ * per 4096 prompt positions) hands to the per-head final stage.  256-byte alignment. */
 int maskkv_select_workspace_bytes(const maskkv_desc* desc, size_t* bytes);
 
 /*

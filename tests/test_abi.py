@@ -46,11 +46,11 @@ def test_strerror(mk):
 def test_workspace_sizes(mk):
     d = mk.Desc(B=1, H=32, d=128, dtype=mk.MASKKV_BF16, n_resp=256, P_max=32768)
     assert mk.maskkv_score_workspace_bytes(d) > 32 * 256 * 4
-    assert mk.maskkv_select_workspace_bytes(d) == 0
+    assert mk.maskkv_select_workspace_bytes(d) == 32 * 32768 * 8  # (key, position) candidates, 4096 per chunk
     assert mk.maskkv_attend_workspace_bytes(d, False) == 0
     assert mk.maskkv_attend_workspace_bytes(d, True) > 0
     long = mk.Desc(B=2, H=4, d=128, dtype=mk.MASKKV_BF16, n_resp=8, P_max=100000)
-    assert mk.maskkv_select_workspace_bytes(long) == 2 * 4 * 100000 * 4
+    assert mk.maskkv_select_workspace_bytes(long) == 2 * 4 * 25 * 4096 * 8
 
 
 @pytest.mark.parametrize("kw,status", [

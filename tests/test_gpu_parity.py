@@ -200,13 +200,13 @@ def test_select_standalone_is_bit_exact():
             assert np.array_equal(keeps[bh], ref), f"window {window} mode {name} bh {bh}"
 
 
-def test_select_long_prompt_uses_global_key_buffer():
-    """Prompts longer than the LDS key buffer take the global-scratch path; still bit-exact."""
+def test_select_long_prompt_reads_candidates_in_place():
+    """Prompts longer than the LDS key buffer: the final stage reads the chunk candidates in place; still bit-exact."""
     m = hp.mk()
     rng = np.random.default_rng(6)
     P = 50000
     desc = m.Desc(B=1, H=2, d=128, dtype=m.MASKKV_BF16, n_resp=8, P_max=P)
-    assert m.maskkv_select_workspace_bytes(desc) == 2 * P * 4
+    assert m.maskkv_select_workspace_bytes(desc) == 2 * 13 * 4096 * 8
     sc = (rng.random((2, P)) ** 4).astype(np.float32)
     budgets = np.array([1234, 40000], dtype=np.int32)
     idx = torch.full((int(budgets.sum()),), -1, dtype=torch.int32, device="cuda")
@@ -228,7 +228,7 @@ def test_select_capacity_is_never_overrun():
     cap = 250
     idx = torch.full((cap + 64,), -7, dtype=torch.int32, device="cuda")
     cu = torch.zeros(5, dtype=torch.int32, device="cuda")
-    m.maskkv_select(desc, sc, 512, 1, 0, bud, idx, cu, cap, None)
+    m.maskkv_select(desc, sc, 512, 1, 0, bud, idx, cu, cap, hp.workspace(m.maskkv_select_workspace_bytes(desc)))
     torch.cuda.synchronize()
     assert cu.cpu().tolist() == [0, 100, 200, 300, 400]
     assert (idx[cap:] == -7).all() and (idx[:cap] >= 0).all()
@@ -259,7 +259,8 @@ def test_head_budgets_on_device():
     # and the budgets feed select directly
     idx = torch.zeros(8 * 256, dtype=torch.int32, device="cuda")
     cu = torch.zeros(9, dtype=torch.int32, device="cuda")
-    m.maskkv_select(batch.desc, scores, scores.stride(0), 7, 0, bud, idx, cu, 8 * 256, None)
+    m.maskkv_select(batch.desc, scores, scores.stride(0), 7, 0, bud, idx, cu, 8 * 256,
+                    hp.workspace(m.maskkv_select_workspace_bytes(batch.desc)))
     torch.cuda.synchronize()
     assert cu.cpu().numpy().tolist() == np.concatenate([[0], np.cumsum(got)]).tolist()
 
