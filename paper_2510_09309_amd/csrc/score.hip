@@ -25,20 +25,24 @@ namespace maskkv {
 
 namespace {
 
-constexpr int kScoreThreads = 256;
-constexpr int kScoreWaves = 4;
-constexpr int kQPerWave = 64;                          // two 32-row MFMA blocks
-constexpr int kQPerGroup = kScoreWaves * kQPerWave;    // queries covered per sweep of a segment
+constexpr int kQPerGroup = 256;                        // queries covered per sweep of a segment
 constexpr int kTargetGroups = 512;                     // about two resident workgroups per compute unit
 constexpr float kLazyLimit = 1.152921504606847e18f;    // 2^60: pass 1 re-centres its reference beyond this
 
-template <typename T, int D>
+template <typename T, int D, int PASS>
 struct ScoreCfg {
+  // Wave shape: bf16 pass 1 runs eight waves of 32 queries (four waves per SIMD with two workgroups per
+  // compute unit; measured faster there), every other case four waves of 64 queries (two per SIMD).
+  static constexpr int kNQ = (sizeof(T) == 2 && PASS == 1) ? 1 : 2;  // 32-query MFMA blocks per wave
+  static constexpr int kWaves = kQPerGroup / (32 * kNQ);
+  static constexpr int kThreads = 64 * kWaves;
+  static constexpr int kWavesPerSimd = kWaves / 2;
+  static constexpr int kQPerWave = 32 * kNQ;
   static constexpr int kRowB = D * (int)sizeof(T);     // bytes per K row
   static constexpr int kRowP = kRowB + 16;             // padded LDS row: conflict-free 16-byte reads
   static constexpr int kSteps = kRowB / 32;            // fragments per row
   static constexpr int kTK = 64;                       // keys per tile: two 32-key blocks
-  static constexpr int kPieces = kTK * kRowB / 16 / kScoreThreads;  // 16-byte pieces per thread per tile
+  static constexpr int kPieces = kTK * kRowB / 16 / kThreads;  // 16-byte pieces per thread per tile
   static constexpr int kPiecesPerRow = kRowB / 16;
   static constexpr int kTileBytes = kTK * kRowP;
   static constexpr int kLdsBytes = 2 * kTileBytes;     // double-buffered K tile (dynamic LDS)
@@ -70,13 +74,13 @@ struct ScoreParams {
 
 __device__ __forceinline__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-template <typename T, int D>
+template <typename T, int D, int PASS>
 __device__ __forceinline__ void load_tile_global(const char* kbase, int64_t stride_t, int key0, int klast,
-                                                 u32x4 (&regs)[ScoreCfg<T, D>::kPieces]) {
-  using C = ScoreCfg<T, D>;
+                                                 u32x4 (&regs)[ScoreCfg<T, D, PASS>::kPieces]) {
+  using C = ScoreCfg<T, D, PASS>;
 #pragma unroll
   for (int i = 0; i < C::kPieces; ++i) {
-    const int p = threadIdx.x + i * kScoreThreads;
+    const int p = threadIdx.x + i * C::kThreads;
     const int row = p / C::kPiecesPerRow;
     const int col = p % C::kPiecesPerRow;
     const int key = min(key0 + row, klast);  // rows past the segment end re-read its last valid row
@@ -84,12 +88,12 @@ __device__ __forceinline__ void load_tile_global(const char* kbase, int64_t stri
   }
 }
 
-template <typename T, int D>
-__device__ __forceinline__ void store_tile_lds(char* buf, const u32x4 (&regs)[ScoreCfg<T, D>::kPieces]) {
-  using C = ScoreCfg<T, D>;
+template <typename T, int D, int PASS>
+__device__ __forceinline__ void store_tile_lds(char* buf, const u32x4 (&regs)[ScoreCfg<T, D, PASS>::kPieces]) {
+  using C = ScoreCfg<T, D, PASS>;
 #pragma unroll
   for (int i = 0; i < C::kPieces; ++i) {
-    const int p = threadIdx.x + i * kScoreThreads;
+    const int p = threadIdx.x + i * C::kThreads;
     const int row = p / C::kPiecesPerRow;
     const int col = p % C::kPiecesPerRow;
     *reinterpret_cast<u32x4*>(buf + row * C::kRowP + col * 16) = regs[i];
@@ -98,10 +102,10 @@ __device__ __forceinline__ void store_tile_lds(char* buf, const u32x4 (&regs)[Sc
 
 // PASS 1: row statistics.  PASS 2: column sums.
 template <typename T, int D, int PASS>
-__global__ __launch_bounds__(kScoreThreads, 2) void score_kernel(const ScoreParams prm) {
-  using C = ScoreCfg<T, D>;
+__global__ __launch_bounds__((ScoreCfg<T, D, PASS>::kThreads), (ScoreCfg<T, D, PASS>::kWavesPerSimd)) void score_kernel(const ScoreParams prm) {
+  using C = ScoreCfg<T, D, PASS>;
   extern __shared__ __attribute__((aligned(16))) char kt_raw[];  // two K tiles
-  __shared__ float cs[3][kScoreWaves][C::kTK];  // pass 2: per-wave column partials of the last three tiles
+  __shared__ float cs[3][C::kWaves][C::kTK];  // pass 2: per-wave column partials of the last three tiles
   __shared__ float nlse[kQPerGroup];            // pass 2: -lse2 of the current query group
 
   const int lane = threadIdx.x & 63;
@@ -114,8 +118,8 @@ __global__ __launch_bounds__(kScoreThreads, 2) void score_kernel(const ScorePara
   int s = blockIdx.x * map.R;
   const int e = min(map.T, s + map.R);
   int cur_bh = -1, cur_qg = -1;
-  u32x4 qf[2][C::kSteps];
-  f32x16 nb[2];  // pass 2: -lse2 / c of this lane's query rows, the initial value of every logits block
+  u32x4 qf[C::kNQ][C::kSteps];
+  f32x16 nb[C::kNQ];  // pass 2: -lse2 / c of this lane's query rows, the initial value of every logits block
 
   while (s < e) {
     // ---- locate the segment that starts at global tile s
@@ -141,7 +145,7 @@ __global__ __launch_bounds__(kScoreThreads, 2) void score_kernel(const ScorePara
     const int64_t kstride = prm.K.stride_t;
 
     for (int qg = 0; qg < prm.n_query; qg += kQPerGroup) {
-      const int q0 = qg + wave * kQPerWave;
+      const int q0 = qg + wave * C::kQPerWave;
       if (bh != cur_bh || qg != cur_qg) {
         cur_bh = bh;
         cur_qg = qg;
@@ -150,7 +154,7 @@ __global__ __launch_bounds__(kScoreThreads, 2) void score_kernel(const ScorePara
         // probabilities are forced to zero through nb = -inf (pass 2).
         const char* qbase = prm.Q.row(b, h, 0);
 #pragma unroll
-        for (int blk = 0; blk < 2; ++blk) {
+        for (int blk = 0; blk < C::kNQ; ++blk) {
           const int q = min(q0 + blk * 32 + r, prm.n_query - 1);
 #pragma unroll
           for (int ks = 0; ks < C::kSteps; ++ks)
@@ -162,91 +166,96 @@ __global__ __launch_bounds__(kScoreThreads, 2) void score_kernel(const ScorePara
           nlse[threadIdx.x] = q < prm.n_query ? -prm.lse2[(int64_t)bh * prm.n_query + q] : -INFINITY;
           __syncthreads();
 #pragma unroll
-          for (int blk = 0; blk < 2; ++blk)
+          for (int blk = 0; blk < C::kNQ; ++blk)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) nb[blk][i] = nlse[wave * kQPerWave + blk * 32 + 8 * (i / 4) + 4 * g + (i % 4)] / c;
+            for (int i = 0; i < 16; ++i) nb[blk][i] = nlse[wave * C::kQPerWave + blk * 32 + 8 * (i / 4) + 4 * g + (i % 4)] / c;
         }
       }
 
       // pass 1 state: this lane's (reference exponent, sum) for query q0 + 32*blk + r over the keys it sees
-      float run_m[2] = {kNegBig, kNegBig};
-      float run_l[2] = {0.f, 0.f};
+      float run_m[C::kNQ], run_l[C::kNQ];
+#pragma unroll
+      for (int blk = 0; blk < C::kNQ; ++blk) {
+        run_m[blk] = kNegBig;
+        run_l[blk] = 0.f;
+      }
 
       float* out = prm.scores + (int64_t)bh * prm.score_stride;
       auto flush = [&](int t) {  // tile t of this segment: add the four waves' partials, write scores
         const int j = k0 + t * C::kTK + (int)threadIdx.x;
         if ((int)threadIdx.x < C::kTK && j < k1) {
-          const float v = cs[t % 3][0][threadIdx.x] + cs[t % 3][1][threadIdx.x] + cs[t % 3][2][threadIdx.x] +
-                          cs[t % 3][3][threadIdx.x];
+          float v = 0.f;
+#pragma unroll
+          for (int w = 0; w < C::kWaves; ++w) v += cs[t % 3][w][threadIdx.x];
           out[j] = qg == 0 ? v : out[j] + v;
         }
       };
 
       // Logits of one 32-key block (both 32-query blocks of this wave) on the matrix pipe.
-      auto form = [&](const char* buf, int kb, f32x16& a0, f32x16& a1) {
+      auto form = [&](const char* buf, int kb, f32x16 (&a)[C::kNQ]) {
         // Pass 2 starts every block from -lse/c of its query rows: the matrix pipe then delivers s - lse/c
         // and the vector pipe is left with one multiply, one exponential and one add per logit.
-        a0 = PASS == 2 ? nb[0] : f32x16{};
-        a1 = PASS == 2 ? nb[1] : f32x16{};
+#pragma unroll
+        for (int blk = 0; blk < C::kNQ; ++blk) a[blk] = PASS == 2 ? nb[blk] : f32x16{};
 #pragma unroll
         for (int ks = 0; ks < C::kSteps; ++ks) {
           const u32x4 kf = *reinterpret_cast<const u32x4*>(buf + (kb * 32 + r) * C::kRowP + ks * 32 + g * 16);
-          if (PASS == 1) {  // S^T block: keys on rows, queries on columns
-            mfma_step<T>(kf, qf[0][ks], a0);
-            mfma_step<T>(kf, qf[1][ks], a1);
-          } else {          // S block: queries on rows, keys on columns
-            mfma_step<T>(qf[0][ks], kf, a0);
-            mfma_step<T>(qf[1][ks], kf, a1);
+#pragma unroll
+          for (int blk = 0; blk < C::kNQ; ++blk) {
+            if (PASS == 1)
+              mfma_step<T>(kf, qf[blk][ks], a[blk]);  // S^T block: keys on rows, queries on columns
+            else
+              mfma_step<T>(qf[blk][ks], kf, a[blk]);  // S block: queries on rows, keys on columns
           }
         }
       };
       // Exponentials and sums of one formed block on the vector pipe.  MASKED is only needed for the last
       // tile of a segment (rows past the segment end re-read its last row and must not be counted).
-      auto reduce = [&](auto masked, int t, int kb, f32x16& a0, f32x16& a1) {
+      auto reduce = [&](auto masked, int t, int kb, f32x16 (&a)[C::kNQ]) {
         if (PASS == 1) {
           if (decltype(masked)::value) {
             const int nvalid = k1 - (k0 + t * C::kTK + kb * 32);  // rows >= nvalid are past the segment end
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const int row = 8 * (i / 4) + 4 * g + (i % 4);
-              if (row >= nvalid) {
-                a0[i] = -INFINITY;
-                a1[i] = -INFINITY;
-              }
-            }
+            for (int blk = 0; blk < C::kNQ; ++blk)
+#pragma unroll
+              for (int i = 0; i < 16; ++i)
+                if (8 * (i / 4) + 4 * g + (i % 4) >= nvalid) a[blk][i] = -INFINITY;
           }
           // Exponentials against the current reference; the reference is only moved (slow path) when a sum
           // leaves the safe range, which also covers the very first block (reference = -1e30).  One
-          // branch per block pair, after all the vector work, keeps the fast path a single basic block.
-          float s0 = 0.f, s1 = 0.f;
+          // branch per stage, after all the vector work, keeps the fast path a single basic block.
+          float sum[C::kNQ];
+          bool ok = true;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) s0 += fast_exp2(fmaf(a0[i], c, -run_m[0]));
+          for (int blk = 0; blk < C::kNQ; ++blk) {
+            sum[blk] = 0.f;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) s1 += fast_exp2(fmaf(a1[i], c, -run_m[1]));
-          if (__all(s0 < kLazyLimit && s1 < kLazyLimit)) {
-            run_l[0] += s0;
-            run_l[1] += s1;
+            for (int i = 0; i < 16; ++i) sum[blk] += fast_exp2(fmaf(a[blk][i], c, -run_m[blk]));
+            ok = ok && sum[blk] < kLazyLimit;
+          }
+          if (__all(ok)) {
+#pragma unroll
+            for (int blk = 0; blk < C::kNQ; ++blk) run_l[blk] += sum[blk];
           } else {
 #pragma unroll
-            for (int blk = 0; blk < 2; ++blk) {
-              const f32x16& a = blk ? a1 : a0;
-              float bm = a[0];
+            for (int blk = 0; blk < C::kNQ; ++blk) {
+              float bm = a[blk][0];
 #pragma unroll
-              for (int i = 1; i < 16; ++i) bm = fmaxf(bm, a[i]);
+              for (int i = 1; i < 16; ++i) bm = fmaxf(bm, a[blk][i]);
               const float m_new = fmaxf(run_m[blk], bm * c);
-              float sum = 0.f;
+              float s2 = 0.f;
 #pragma unroll
-              for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(a[i], c, -m_new));
-              run_l[blk] = run_l[blk] * fast_exp2(run_m[blk] - m_new) + sum;
+              for (int i = 0; i < 16; ++i) s2 += fast_exp2(fmaf(a[blk][i], c, -m_new));
+              run_l[blk] = run_l[blk] * fast_exp2(run_m[blk] - m_new) + s2;
               run_m[blk] = m_new;
             }
           }
         } else {
           float colsum = 0.f;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) colsum += fast_exp2(a0[i] * c);
+          for (int blk = 0; blk < C::kNQ; ++blk)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) colsum += fast_exp2(a1[i] * c);
+            for (int i = 0; i < 16; ++i) colsum += fast_exp2(a[blk][i] * c);
           colsum += xor32(colsum);
           if (g == 0) cs[t % 3][wave][kb * 32 + r] = colsum;
         }
@@ -259,23 +268,23 @@ __global__ __launch_bounds__(kScoreThreads, 2) void score_kernel(const ScorePara
       //   tile t+1: registers -> LDS, barrier, request tile t+2 from global memory
       //   stage 2 of iteration t: form (t+1,0) -> A  |  reduce (t,1) from B
       u32x4 stage[C::kPieces];
-      f32x16 accA0, accA1, accB0, accB1;
+      f32x16 accA[C::kNQ], accB[C::kNQ];
       __syncthreads();  // the previous segment's readers are done with the tile and partial buffers
-      load_tile_global<T, D>(kbase, kstride, k0, k1 - 1, stage);
-      store_tile_lds<T, D>(kt_raw, stage);
-      if (nt > 1) load_tile_global<T, D>(kbase, kstride, k0 + C::kTK, k1 - 1, stage);
+      load_tile_global<T, D, PASS>(kbase, kstride, k0, k1 - 1, stage);
+      store_tile_lds<T, D, PASS>(kt_raw, stage);
+      if (nt > 1) load_tile_global<T, D, PASS>(kbase, kstride, k0 + C::kTK, k1 - 1, stage);
       __syncthreads();
-      form(kt_raw, 0, accA0, accA1);
+      form(kt_raw, 0, accA);
 
       auto iteration = [&](auto masked, int t) {
-        form(kt_raw + (t & 1) * C::kTileBytes, 1, accB0, accB1);
-        reduce(masked, t, 0, accA0, accA1);
-        if (t + 1 < nt) store_tile_lds<T, D>(kt_raw + ((t + 1) & 1) * C::kTileBytes, stage);
+        form(kt_raw + (t & 1) * C::kTileBytes, 1, accB);
+        reduce(masked, t, 0, accA);
+        if (t + 1 < nt) store_tile_lds<T, D, PASS>(kt_raw + ((t + 1) & 1) * C::kTileBytes, stage);
         __syncthreads();  // tile t+1 is visible; every wave is done reading tile t-1 and reducing into cs[(t-1)%3]
-        if (t + 2 < nt) load_tile_global<T, D>(kbase, kstride, k0 + (t + 2) * C::kTK, k1 - 1, stage);
+        if (t + 2 < nt) load_tile_global<T, D, PASS>(kbase, kstride, k0 + (t + 2) * C::kTK, k1 - 1, stage);
         if (PASS == 2 && t > 0) flush(t - 1);
-        if (t + 1 < nt) form(kt_raw + ((t + 1) & 1) * C::kTileBytes, 0, accA0, accA1);
-        reduce(masked, t, 1, accB0, accB1);
+        if (t + 1 < nt) form(kt_raw + ((t + 1) & 1) * C::kTileBytes, 0, accA);
+        reduce(masked, t, 1, accB);
       };
       for (int t = 0; t + 1 < nt; ++t) iteration(std::false_type{}, t);
       if (PASS == 1 && k1 - k0 < nt * C::kTK)
@@ -291,7 +300,7 @@ __global__ __launch_bounds__(kScoreThreads, 2) void score_kernel(const ScorePara
         const int part = (int)blockIdx.x - region_start / map.R;
         const int slot = bh * (prm.parts_p + prm.parts_r) + (prompt ? 0 : prm.parts_p) + part;
 #pragma unroll
-        for (int blk = 0; blk < 2; ++blk) {
+        for (int blk = 0; blk < C::kNQ; ++blk) {
           const float m_o = xor32(run_m[blk]);
           const float l_o = xor32(run_l[blk]);
           const float m = fmaxf(run_m[blk], m_o);
@@ -399,7 +408,7 @@ int mark(void* const* events, int i, hipStream_t stream) {
 
 template <typename T, int D, int PASS>
 int launch_pass(const ScoreParams& prm, hipStream_t stream) {
-  using C = ScoreCfg<T, D>;
+  using C = ScoreCfg<T, D, PASS>;
   static bool raised = false;  // one-time opt-in to more than the default dynamic LDS size
   if (C::kLdsBytes > 48 * 1024 && !raised) {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<T, D, PASS>),
@@ -412,7 +421,7 @@ int launch_pass(const ScoreParams& prm, hipStream_t stream) {
     raised = true;
   }
   const dim3 grid((prm.map.T + prm.map.R - 1) / prm.map.R);
-  hipLaunchKernelGGL((score_kernel<T, D, PASS>), grid, dim3(kScoreThreads), C::kLdsBytes, stream, prm);
+  hipLaunchKernelGGL((score_kernel<T, D, PASS>), grid, dim3(C::kThreads), C::kLdsBytes, stream, prm);
   return check_launch(PASS == 1 ? "score pass 1" : "score pass 2");
 }
 
