@@ -163,7 +163,8 @@ __global__ __launch_bounds__((ScoreCfg<T, D, PASS>::kThreads), (ScoreCfg<T, D, P
         if (PASS == 2) {
           __syncthreads();
           const int q = qg + (int)threadIdx.x;
-          nlse[threadIdx.x] = q < prm.n_query ? -prm.lse2[(int64_t)bh * prm.n_query + q] : -INFINITY;
+          if ((int)threadIdx.x < kQPerGroup)
+            nlse[threadIdx.x] = q < prm.n_query ? -prm.lse2[(int64_t)bh * prm.n_query + q] : -INFINITY;
           __syncthreads();
 #pragma unroll
           for (int blk = 0; blk < C::kNQ; ++blk)

@@ -16,7 +16,8 @@
 // single key).  Scanning everything with LDS atomics is slow when almost every key falls into the same few
 // bins (a flat background under a few large scores), so the refinement normally runs on a short candidate
 // list: every thread remembers the largest keys among those it handled; the k-th largest of those 1024*c
-// remembered keys (c = ceil(k/1024)) is a lower bound t0 of tau, because they are a subset of the keys;
+// remembered keys (c = ceil(k/1024)), or the lower edge of the histogram bin that holds it, is a lower bound
+// t0 of tau, because they are a subset of the keys;
 // the keys >= t0 - typically little more than k of them - are the candidates.  Inputs with k > 4096, or
 // whose candidates do not fit the list, take the whole-array path.
 // The kept set is "key > tau" plus the first (k - count_gt) entries with key == tau, emitted in
@@ -235,8 +236,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
 
   // ---- range refinement until a single key remains.  State in LDS: the key range [sh_lo, sh_hi], the rank
   // sh_krem wanted inside it, and sh_nlist (>= 0: scan list[0..sh_nlist), < 0: scan all n keys).
-  auto refine = [&]() {
-    for (int round = 0; round < 4; ++round) {
+  auto refine = [&](int max_rounds) {
+    for (int round = 0; round < max_rounds; ++round) {
       const uint32_t lo = sh_lo, hi = sh_hi;
       const int krem = sh_krem;
       const int nlist = sh_nlist;
@@ -282,6 +283,20 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
           sh_hi = (uint32_t)min((uint64_t)hi, (uint64_t)nlo + span);
           sh_krem = krem - above;
           sh_bincount = in0 ? h0 : h1;
+        }
+        __syncthreads();
+      }
+      // A bin with a single key: that key is the answer, fetch it instead of refining the bin further.
+      if (sh_bincount == 1 && sh_lo != sh_hi) {
+        const uint32_t nlo = sh_lo, nhi = sh_hi;
+        __syncthreads();
+        const int cnt = nlist < 0 ? n : nlist;
+        for (int e = tid; e < cnt; e += kSelThreads) {
+          const uint32_t key = nlist < 0 ? key_at(e) : list[e];
+          if (key >= nlo && key <= nhi) {
+            sh_lo = key;
+            sh_hi = key;
+          }
         }
         __syncthreads();
       }
@@ -332,7 +347,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
       sh_nlist = kSelThreads * c;
     }
     __syncthreads();
-    refine();
+    refine(1);  // one round is enough here: the lower edge of the chosen bin is a lower bound as well
     const uint32_t t0 = sh_lo;
     __syncthreads();  // everyone has read t0 and is done with the remembered keys
     if (tid == 0) sh_nlist = 0;
@@ -361,7 +376,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
     }
     __syncthreads();
   }
-  refine();
+  refine(4);
   const uint32_t tau = sh_lo;
   const int need_eq = sh_krem;  // how many entries equal to tau are kept (lowest first)
 
