@@ -74,6 +74,7 @@ def test_bad_call_arguments_are_rejected_before_launch(mk):
     good = mk._CTensor(fake, 0, 108 * 64, 64, None)
     misaligned = mk._CTensor(fake + 4, 0, 108 * 64, 64, None)
     short_row = mk._CTensor(fake, 0, 108 * 64, 32, None)
+    huge_stride = mk._CTensor(fake, 0, 0, (1 << 24) // 2 + 8, None)   # token stride above 16 MiB in bytes
     null = mk._CTensor(0, 0, 0, 64, None)
     f = ct.c_void_p(fake)
     call_score = lambda q, k, stride, ws, wsn: lib.maskkv_score(
@@ -81,6 +82,8 @@ def test_bad_call_arguments_are_rejected_before_launch(mk):
     assert call_score(null, good, 128, f, 1 << 20) == 1
     assert call_score(good, misaligned, 128, f, 1 << 20) == 1
     assert call_score(good, short_row, 128, f, 1 << 20) == 1
+    assert call_score(good, huge_stride, 128, f, 1 << 20) == 1
+    assert b"16 MiB" in lib.maskkv_last_error()
     assert call_score(good, good, 64, f, 1 << 20) == 1          # score_stride < P_max
     assert call_score(good, good, 128, None, 0) == 4            # no workspace
     assert call_score(good, good, 128, f, 16) == 4              # too small
