@@ -27,6 +27,7 @@ namespace {
 
 constexpr int kQPerGroup = 256;                        // queries covered per sweep of a segment
 constexpr int kTargetGroups = 512;                     // about two resident workgroups per compute unit
+constexpr double kSkew = 1.7;                          // tile share of an early workgroup relative to a late one
 constexpr float kLazyLimit = 1.152921504606847e18f;    // 2^60: pass 1 re-centres its reference beyond this
 
 template <typename T, int D, int PASS>
@@ -52,7 +53,12 @@ struct ScoreCfg {
 struct TileMap {
   int tk;                         // keys per tile
   int with_resp;                  // 1: response tiles are part of the index space (pass 1)
-  int R;                          // tiles per workgroup
+  int R;                          // tiles per workgroup, first G1 workgroups
+  int R2;                         // tiles per workgroup, the others (R2 <= R)
+  int G1;                         // see make_map
+  int G;                          // workgroups in total
+  __host__ __device__ int first_tile(int g) const { return g < G1 ? g * R : G1 * R + (g - G1) * R2; }
+  __host__ __device__ int group_of(int tile) const { return tile < G1 * R ? tile / R : G1 + (tile - G1 * R) / R2; }
   int T;                          // tiles in total
   int toff[MASKKV_MAX_BATCH + 1]; // first global tile of sequence b (all its heads)
 };
@@ -115,8 +121,8 @@ __global__ __launch_bounds__((ScoreCfg<T, D, PASS>::kThreads), (ScoreCfg<T, D, P
   const float c = prm.c;
   const TileMap& map = prm.map;
 
-  int s = blockIdx.x * map.R;
-  const int e = min(map.T, s + map.R);
+  int s = map.first_tile(blockIdx.x);
+  const int e = min(map.T, map.first_tile(blockIdx.x + 1));
   int cur_bh = -1, cur_qg = -1;
   u32x4 qf[C::kNQ][C::kSteps];
   f32x16 nb[C::kNQ];  // pass 2: -lse2 / c of this lane's query rows, the initial value of every logits block
@@ -298,7 +304,7 @@ __global__ __launch_bounds__((ScoreCfg<T, D, PASS>::kThreads), (ScoreCfg<T, D, P
       }
 
       if (PASS == 1) {
-        const int part = (int)blockIdx.x - region_start / map.R;
+        const int part = (int)blockIdx.x - map.group_of(region_start);
         const int slot = bh * (prm.parts_p + prm.parts_r) + (prompt ? 0 : prm.parts_p) + part;
 #pragma unroll
         for (int blk = 0; blk < C::kNQ; ++blk) {
@@ -328,8 +334,8 @@ __global__ __launch_bounds__(256) void score_merge_kernel(const ScoreParams prm)
   const int nrt = ceil_div(prm.n_resp, map.tk);
   const int a_p = map.toff[b] + h * (npt + nrt);
   const int a_r = a_p + npt;
-  const int np_parts = npt > 0 ? (a_p + npt - 1) / map.R - a_p / map.R + 1 : 0;
-  const int nr_parts = (a_r + nrt - 1) / map.R - a_r / map.R + 1;
+  const int np_parts = npt > 0 ? map.group_of(a_p + npt - 1) - map.group_of(a_p) + 1 : 0;
+  const int nr_parts = map.group_of(a_r + nrt - 1) - map.group_of(a_r) + 1;
   const int nslot = prm.parts_p + prm.parts_r;
   float mass = 0.f;
   for (int q = threadIdx.x; q < prm.n_query; q += 256) {
@@ -385,8 +391,17 @@ TileMap make_map(const maskkv_desc* d, const Lens& lens, bool with_resp) {
   }
   for (int b = d->B; b <= MASKKV_MAX_BATCH; ++b) m.toff[b] = t;
   m.T = t;
-  m.R = (t + kTargetGroups - 1) / kTargetGroups;
-  if (m.R < 1) m.R = 1;
+  // About two workgroups per compute unit are launched and all are resident at once.  The hardware favours
+  // the older of the two workgroups that share a compute unit, so with equal shares the first half of the
+  // grid finishes early and the second half then runs alone at lower efficiency: the first G1 workgroups
+  // (one per compute unit in dispatch order) get kSkew times the tiles of the others (1.7 measured best at the
+  // 32k-prompt shape: both halves then finish within a few percent of each other).
+  m.G1 = kTargetGroups / 2;
+  m.R2 = (int)((double)t / (m.G1 * (1.0 + kSkew)) + 0.999);
+  if (m.R2 < 1) m.R2 = 1;
+  m.R = (t - m.G1 * m.R2 + m.G1 - 1) / m.G1;
+  if (m.R < m.R2) m.R = m.R2;
+  m.G = t <= m.G1 * m.R ? (t + m.R - 1) / m.R : m.G1 + (t - m.G1 * m.R + m.R2 - 1) / m.R2;
   return m;
 }
 
@@ -395,8 +410,8 @@ void stat_slots(const maskkv_desc* d, const Lens& lens, const TileMap& map1, int
   int npt_max = 0;
   for (int b = 0; b < d->B; ++b) npt_max = max(npt_max, (lens.P[b] + map1.tk - 1) / map1.tk);
   const int nrt = (d->n_resp + map1.tk - 1) / map1.tk;
-  *parts_p = (npt_max + map1.R - 1) / map1.R + 1;
-  *parts_r = (nrt + map1.R - 1) / map1.R + 1;
+  *parts_p = (npt_max + map1.R2 - 1) / map1.R2 + 1;
+  *parts_r = (nrt + map1.R2 - 1) / map1.R2 + 1;
 }
 
 int mark(void* const* events, int i, hipStream_t stream) {
@@ -421,7 +436,7 @@ int launch_pass(const ScoreParams& prm, hipStream_t stream) {
     }
     raised = true;
   }
-  const dim3 grid((prm.map.T + prm.map.R - 1) / prm.map.R);
+  const dim3 grid(prm.map.G);
   hipLaunchKernelGGL((score_kernel<T, D, PASS>), grid, dim3(C::kThreads), C::kLdsBytes, stream, prm);
   return check_launch(PASS == 1 ? "score pass 1" : "score pass 2");
 }
