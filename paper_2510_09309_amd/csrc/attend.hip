@@ -39,7 +39,7 @@ struct AttendParams {
   const char* Vc;
   const int32_t* cu;
   int64_t capacity;
-  int H, n_resp, full, n_splits;
+  int H, BH, n_resp, full, n_splits;
   float c;  // scale * log2(e)
   float* lse;
   float* part_o;     // [BH][n_splits][n_resp][D]
@@ -307,6 +307,201 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const AttendParams 
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Narrow launches (few heads x query tiles, bf16): the kernel above would occupy a fraction of the compute
+// units with one long serial chain of tiles each.  Here a workgroup serves 32 queries and its four waves
+// split the key axis: wave w takes the 32-key blocks w, w+4, ... on its own - K fragments straight from
+// global memory into registers, V through a wave-private transposed LDS tile, no workgroup barrier in the
+// loop - and the four partial (O, m, l) are merged through LDS at the end.  Two blocks per wave are kept in
+// flight.  Workgroups of one head are given indices that are congruent modulo 8, which places them on one
+// XCD, so the head's K/V rows are fetched into one L2 only.
+constexpr int kNarrowVS = 36;  // bf16 elements per transposed-V row: 32 keys + padding
+
+template <int D>
+struct NarrowCfg {
+  static constexpr int kRowB = D * 2;
+  static constexpr int kSteps = kRowB / 32;
+  static constexpr int kPPR = kRowB / 16;        // 16-byte pieces per row
+  static constexpr int kVP = 32 * kPPR / 64;     // V pieces per lane per block
+  static constexpr int kDB = D / 32;
+  static constexpr int kVtBytes = D * kNarrowVS * 2;                       // per wave
+  static constexpr int kMergeBytes = kAttWaves * kDB * 16 * 64 * 4;        // partial O of the four waves
+  static constexpr int kLds = (kMergeBytes > kAttWaves * kVtBytes ? kMergeBytes : kAttWaves * kVtBytes) + kAttWaves * 32 * 8;
+};
+
+template <int D>
+__global__ __launch_bounds__(kAttThreads) void attend_narrow_kernel(const AttendParams prm) {
+  using T = bf16_t;
+  using C = NarrowCfg<D>;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+
+  const int nqt = (prm.n_resp + 31) / 32;
+  const int id = blockIdx.x;
+  const int bh = (id / (8 * nqt)) * 8 + id % 8;
+  const int qt = (id / 8) % nqt;
+  if (bh >= prm.BH) return;
+  const int b = bh / prm.H;
+  const int h = bh % prm.H;
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int r = lane & 31;
+  const int g = lane >> 5;
+
+  const int64_t c0 = min((int64_t)prm.cu[bh], prm.capacity);
+  const int64_t c1 = min((int64_t)prm.cu[bh + 1], prm.capacity);
+  const char* a_k = prm.Kc + c0 * C::kRowB;
+  const char* a_v = prm.Vc + c0 * C::kRowB;
+  const int len_a = (int)(c1 - c0);
+  const int Lk = len_a + prm.n_resp;
+  const int nblk = (Lk + 31) / 32;
+
+  const int q = qt * 32 + r;
+  u32x4 qf[C::kSteps];
+  {
+    const char* qrow = prm.Q.row(b, h, min(q, prm.n_resp - 1));
+#pragma unroll
+    for (int s = 0; s < C::kSteps; ++s) qf[s] = *reinterpret_cast<const u32x4*>(qrow + s * 32 + g * 16);
+  }
+  f32x16 o[C::kDB];
+#pragma unroll
+  for (int db = 0; db < C::kDB; ++db) o[db] = f32x16{};
+  float m = kNegBig, l = 0.f;
+  const float c = prm.c;
+  uint32_t* vt32 = reinterpret_cast<uint32_t*>(smem + wave * C::kVtBytes);
+
+  auto key_row = [&](const char* packed, const View& rest, int j) -> const char* {
+    return j < len_a ? packed + (int64_t)j * C::kRowB : rest.row(b, h, j - len_a);
+  };
+  // Ask for block blk: K in MFMA fragment layout (lane = key row), V as row pieces for the transposition
+  // (item = (key pair, 16-byte slice); pieces 2i and 2i+1 are the pair's two rows).  Rows past the end of
+  // the key axis re-read its last row and are masked.
+  auto request = [&](int blk, u32x4 (&kf)[C::kSteps], u32x4 (&vr)[C::kVP]) {
+    const char* krow = key_row(a_k, prm.K2, min(blk * 32 + r, Lk - 1)) + g * 16;
+#pragma unroll
+    for (int s = 0; s < C::kSteps; ++s) kf[s] = *reinterpret_cast<const u32x4*>(krow + s * 32);
+#pragma unroll
+    for (int i = 0; i < C::kVP / 2; ++i) {
+      const int item = lane + i * 64;
+      const int pair = item / C::kPPR, col = item % C::kPPR;
+      const int j0 = min(blk * 32 + 2 * pair, Lk - 1), j1 = min(blk * 32 + 2 * pair + 1, Lk - 1);
+      vr[2 * i] = *reinterpret_cast<const u32x4*>(key_row(a_v, prm.V2, j0) + col * 16);
+      vr[2 * i + 1] = *reinterpret_cast<const u32x4*>(key_row(a_v, prm.V2, j1) + col * 16);
+    }
+  };
+  auto step = [&](int blk, u32x4 (&kf)[C::kSteps], u32x4 (&vr)[C::kVP]) {
+    // V^T of the block into this wave's LDS tile: a 32-bit word holds keys (2*pair, 2*pair+1) of one element
+#pragma unroll
+    for (int i = 0; i < C::kVP / 2; ++i) {
+      const int item = lane + i * 64;
+      const int pair = item / C::kPPR, col = item % C::kPPR;
+      const u32x4 a = vr[2 * i], bq = vr[2 * i + 1];
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        vt32[(col * 8 + 2 * w) * (kNarrowVS / 2) + pair] = (a[w] & 0xFFFFu) | (bq[w] << 16);
+        vt32[(col * 8 + 2 * w + 1) * (kNarrowVS / 2) + pair] = (a[w] >> 16) | (bq[w] & 0xFFFF0000u);
+      }
+    }
+    // S^T = K Q^T: keys on rows, queries on columns
+    f32x16 s = f32x16{};
+#pragma unroll
+    for (int st = 0; st < C::kSteps; ++st) mfma_step<T>(kf[st], qf[st], s);
+    if (blk + 2 * kAttWaves < nblk) request(blk + 2 * kAttWaves, kf, vr);
+    const int nvalid = Lk - blk * 32;
+    if (nvalid < 32) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        if (8 * (i / 4) + 4 * g + (i % 4) >= nvalid) s[i] = -INFINITY;
+    }
+    // online softmax; lanes l and l^32 hold the same query
+    float bm = s[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) bm = fmaxf(bm, s[i]);
+    bm = fmaxf(bm, xor32(bm));
+    const float m_new = fmaxf(m, bm * c);
+    const float alpha = fast_exp2(m - m_new);
+    float psum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float pv = fast_exp2(fmaf(s[i], c, -m_new));
+      s[i] = pv;
+      psum += pv;
+    }
+    l = l * alpha + psum;
+    m = m_new;
+#pragma unroll
+    for (int db = 0; db < C::kDB; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+    // O^T += V^T P^T
+#pragma unroll
+    for (int tp = 0; tp < 2; ++tp) {
+      u32x4 pf;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) pf[w] = pack_bf16x2(s[8 * tp + 2 * w], s[8 * tp + 2 * w + 1]);
+#pragma unroll
+      for (int db = 0; db < C::kDB; ++db) {
+        const char* rowp = reinterpret_cast<const char*>(vt32) + ((db * 32 + r) * kNarrowVS + 16 * tp + 4 * g) * 2;
+        const u32x2 lo = *reinterpret_cast<const u32x2*>(rowp);
+        const u32x2 hi = *reinterpret_cast<const u32x2*>(rowp + 16);
+        const u32x4 vf = {lo[0], lo[1], hi[0], hi[1]};
+        mfma_step<T>(vf, pf, o[db]);
+      }
+    }
+  };
+
+  u32x4 kfa[C::kSteps], vra[C::kVP], kfb[C::kSteps], vrb[C::kVP];
+  if (wave < nblk) request(wave, kfa, vra);
+  if (wave + kAttWaves < nblk) request(wave + kAttWaves, kfb, vrb);
+  for (int blk = wave; blk < nblk; blk += 2 * kAttWaves) {
+    step(blk, kfa, vra);
+    if (blk + kAttWaves < nblk) step(blk + kAttWaves, kfb, vrb);
+  }
+
+  // ---- merge the four waves' partial results through LDS (the V tiles are no longer needed)
+  const float l_tot = l + xor32(l);
+  float* mo = reinterpret_cast<float*>(smem);                              // [wave][db][i][lane]
+  float2* ml = reinterpret_cast<float2*>(smem + C::kLds - kAttWaves * 32 * 8);  // [wave][query]
+  __syncthreads();
+#pragma unroll
+  for (int db = 0; db < C::kDB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) mo[((wave * C::kDB + db) * 16 + i) * 64 + lane] = o[db][i];
+  if (g == 0) ml[wave * 32 + r] = make_float2(m, l_tot);
+  __syncthreads();
+  float M = kNegBig;
+#pragma unroll
+  for (int w = 0; w < kAttWaves; ++w) M = fmaxf(M, ml[w * 32 + r].x);
+  float wgt[kAttWaves];
+  float L = 0.f;
+#pragma unroll
+  for (int w = 0; w < kAttWaves; ++w) {
+    const float2 v = ml[w * 32 + r];
+    wgt[w] = fast_exp2(v.x - M);
+    L += wgt[w] * v.y;
+  }
+  if (q >= prm.n_resp) return;
+  const float inv = 1.f / L;
+  char* orow = prm.O.row(b, h, q);
+  for (int db = wave; db < C::kDB; db += kAttWaves) {
+#pragma unroll
+    for (int qd = 0; qd < 4; ++qd) {
+      float v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float acc = 0.f;
+#pragma unroll
+        for (int w = 0; w < kAttWaves; ++w) acc += wgt[w] * mo[((w * C::kDB + db) * 16 + 4 * qd + e) * 64 + lane];
+        v[e] = acc * inv;
+      }
+      u32x2 wout;
+      wout[0] = pack_bf16x2(v[0], v[1]);
+      wout[1] = pack_bf16x2(v[2], v[3]);
+      *reinterpret_cast<u32x2*>(orow + (db * 32 + 8 * qd + 4 * g) * 2) = wout;
+    }
+  }
+  if (prm.lse && wave == 0 && g == 0) prm.lse[(int64_t)bh * prm.n_resp + q] = (M + __log2f(L)) * kLn2;
+}
+
 // Merge the key splits of one query row: O = sum_s w_s O_s / sum_s w_s l_s, w_s = 2^(m_s - max m).
 template <typename T, int D>
 __global__ __launch_bounds__(D) void attend_merge_kernel(const AttendParams prm) {
@@ -346,6 +541,33 @@ int attend_splits(const maskkv_desc* d, bool full) {
   return (int)s;
 }
 
+// The narrow kernel is used when the tiled kernel would launch fewer workgroups than there are compute units.
+bool attend_is_narrow(const maskkv_desc* d, bool full) {
+  if (full || d->dtype != MASKKV_BF16) return false;
+  const int64_t qtiles = (d->n_resp + kQPerBlock - 1) / kQPerBlock;
+  return qtiles * d->B * d->H < 256;
+}
+
+template <int D>
+int launch_attend_narrow(const AttendParams& prm, hipStream_t stream) {
+  using C = NarrowCfg<D>;
+  static bool raised = false;  // one-time opt-in to more than the default dynamic LDS size
+  if (C::kLds > 48 * 1024 && !raised) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_narrow_kernel<D>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, C::kLds);
+    if (e != hipSuccess) {
+      set_error("attend: cannot raise dynamic LDS limit: %s", hipGetErrorString(e));
+      (void)hipGetLastError();
+      return MASKKV_EHIP;
+    }
+    raised = true;
+  }
+  const int nqt = (prm.n_resp + 31) / 32;
+  const int groups = (prm.BH + 7) / 8 * 8 * nqt;
+  hipLaunchKernelGGL((attend_narrow_kernel<D>), dim3(groups), dim3(kAttThreads), C::kLds, stream, prm);
+  return check_launch("attend (narrow)");
+}
+
 template <typename T, int D>
 int launch_attend_t(const AttendParams& prm, int B, hipStream_t stream) {
   const dim3 grid((prm.n_resp + kQPerBlock - 1) / kQPerBlock, prm.n_splits, B * prm.H);
@@ -381,6 +603,7 @@ int launch_attend(const maskkv_desc* d, const Lens& lens, bool full, const View&
   prm.cu = cu_budget;
   prm.capacity = capacity;
   prm.H = d->H;
+  prm.BH = d->B * d->H;
   prm.n_resp = d->n_resp;
   prm.full = full ? 1 : 0;
   prm.n_splits = attend_splits(d, full);
@@ -394,6 +617,8 @@ int launch_attend(const maskkv_desc* d, const Lens& lens, bool full, const View&
     prm.part_ml = reinterpret_cast<float2*>(reinterpret_cast<char*>(workspace) +
                                             (rows * d->d * sizeof(float) + 255) / 256 * 256);
   }
+  if (attend_is_narrow(d, full))
+    return d->d == 128 ? launch_attend_narrow<128>(prm, stream) : launch_attend_narrow<64>(prm, stream);
   if (d->dtype == MASKKV_BF16)
     return d->d == 128 ? launch_attend_t<bf16_t, 128>(prm, d->B, stream) : launch_attend_t<bf16_t, 64>(prm, d->B, stream);
   return d->d == 128 ? launch_attend_t<float, 128>(prm, d->B, stream) : launch_attend_t<float, 64>(prm, d->B, stream);

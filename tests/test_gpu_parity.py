@@ -279,6 +279,29 @@ def test_full_budget_compressed_equals_full_attention_on_gpu():
     assert (lse1 - lse2).abs().max().item() < 1e-4
 
 
+def test_attend_wide_launch_takes_the_tiled_kernel():
+    """B*H*ceil(n_resp/128) >= 256 workgroups: the compressed call runs the tiled kernel (narrower launches
+    run the kernel whose waves split the key axis); both are checked against the oracle elsewhere and here."""
+    B, H = 4, 64
+    layers = [synth.make_layer(900 + b, H=H, d=64, P=200 + 37 * b, n_m=129, dtype="bf16", n_planted=6, amplitude=2.5)
+              for b in range(B)]
+    batch = hp.Batch(layers)
+    assert B * H * 2 >= 256
+    budgets = synth.budgets_log_uniform(B * H, 8, 150, seed=77)
+    scores, _ = hp.gpu_score(batch)
+    idx, cu, cap = hp.gpu_select(batch, scores, budgets, 7)
+    keeps, _ = hp.split_idx(idx, cu)
+    Kc, Vc = hp.gpu_compact(batch, idx, cu, cap)
+    O, lse = hp.gpu_attend(batch, Kc, Vc, cu, cap)
+    O_h, lse_h = O.float().cpu().numpy(), lse.cpu().numpy().reshape(B, H, 129)
+    for b, L in enumerate(layers):
+        for h in (0, 17, 63):
+            keep = keeps[b * H + h]
+            ref, rl = orc.attend(L.Q[h], L.K[h, keep], L.V[h, keep], L.K[h, L.P:], L.V[h, L.P:], return_lse=True)
+            assert np.abs(O_h[b, h] - ref).max() <= hp.ATTEND_ATOL_BF16
+            assert np.abs(lse_h[b, h] - rl).max() <= 1e-3
+
+
 def test_repeated_calls_are_deterministic():
     L = synth.make_layer(83, H=4, d=128, P=5000, n_m=256, dtype="bf16", n_planted=50, amplitude=2.5)
     batch = hp.Batch([L])
