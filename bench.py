@@ -94,6 +94,76 @@ def device_layer(torch, cfg, layer):
     return Q.to(torch.bfloat16), K.to(torch.bfloat16), V.to(torch.bfloat16)
 
 
+def layer_stack(torch, mk, cfg, desc, n_layers, have, stride):
+    """The path over a whole stack of resident layers with immediate layer-by-layer eviction: per layer
+    score -> maskkv_head_budgets (budgets stay on the device) -> select -> compact into the layer's own cache ->
+    attend.  Timed eagerly and as one captured HIP graph; every graph replay is compared with the eager result."""
+    H, d, P, n_m = cfg["H"], cfg["d"], cfg["P"], cfg["n_m"]
+    k_l, alpha = cfg["budget_avg"], 0.1
+    cap = H * k_l
+    layers = list(have) + [device_layer(torch, cfg, l) for l in range(len(have), n_layers)]
+    layers = layers[:n_layers]
+    resp = [(mk.tensor_view(K, seq_start=[P]), mk.tensor_view(V, seq_start=[P])) for (_, K, V) in layers]
+    dev = dict(device="cuda")
+    scores = torch.empty((H, stride), dtype=torch.float32, **dev)
+    mass = [torch.empty(H, dtype=torch.float32, **dev) for _ in layers]
+    budgets = [torch.empty(H, dtype=torch.int32, **dev) for _ in layers]
+    idx = [torch.zeros(cap, dtype=torch.int32, **dev) for _ in layers]
+    cu = [torch.empty(H + 1, dtype=torch.int32, **dev) for _ in layers]
+    Kc = [torch.zeros((cap, d), dtype=torch.bfloat16, **dev) for _ in layers]
+    Vc = [torch.zeros((cap, d), dtype=torch.bfloat16, **dev) for _ in layers]
+    O = [torch.empty((1, H, n_m, d), dtype=torch.bfloat16, **dev) for _ in layers]
+    ws = lambda n: torch.empty(max(n, 256), dtype=torch.uint8, **dev)
+    ws_score, ws_sel = ws(mk.maskkv_score_workspace_bytes(desc)), ws(mk.maskkv_select_workspace_bytes(desc))
+    ws_att = ws(mk.maskkv_attend_workspace_bytes(desc, False))
+
+    def run_stack(stream):
+        for l, (Q, K, V) in enumerate(layers):
+            mk.maskkv_score(desc, Q, K, 0.0, scores, stride, mass[l], ws_score, stream)
+            mk.maskkv_head_budgets(desc, mass[l], k_l, alpha, budgets[l], stream)
+            mk.maskkv_select(desc, scores, stride, cfg["window"], mk.POOL_MEAN, budgets[l], idx[l], cu[l], cap, ws_sel,
+                             stream)
+            mk.maskkv_compact(desc, K, V, idx[l], cu[l], cap, Kc[l], Vc[l], stream)
+            mk.maskkv_attend(desc, Q, Kc[l], Vc[l], cu[l], cap, resp[l][0], resp[l][1], 0.0, O[l], None, ws_att, stream)
+
+    def timed(fn, reps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    cur = torch.cuda.current_stream()
+    run_stack(cur)                      # warm-up (also the one-time kernel attribute calls)
+    ms_eager = timed(lambda: run_stack(cur), 3)
+    want = [(idx[l].clone(), O[l].clone()) for l in (0, n_layers - 1)]
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(cur)
+    with torch.cuda.graph(graph, stream=side):
+        run_stack(torch.cuda.current_stream())
+    ok = True
+    for _ in range(3):                  # replays with eager work and synchronisation in between
+        for l in (0, n_layers - 1):
+            idx[l].zero_()
+            O[l].zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ok = ok and all(torch.equal(idx[l], w[0]) and torch.equal(O[l], w[1])
+                        for l, w in zip((0, n_layers - 1), want))
+    ms_graph = timed(graph.replay, 3)
+    kept = [int(c[-1].item()) for c in cu]
+    return {"layers": n_layers, "ms_eager": ms_eager, "ms_graph": ms_graph, "graph_replays_match_eager": bool(ok),
+            "prompt_tokens_per_s_whole_stack": P / (min(ms_eager, ms_graph) * 1e-3),
+            "budgets": f"on-device head budgets, k_l={k_l}, alpha={alpha}",
+            "kept_rows_per_layer_min_max": [min(kept), max(kept)], "capacity_per_layer": cap}
+
+
 def cpu_oracle_baseline(cfg, budget_seconds=15.0):
     """Time the float64 oracle (score+pool+select+compact+attend) head by head on the host cores."""
     import torch
@@ -132,6 +202,10 @@ def main():
     ap.add_argument("--workload", default="C4", choices=sorted(WORKLOADS))
     ap.add_argument("--resident-layers", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stack-layers", type=int, default=32,
+                    help="after the timed region, also run a whole stack of this many resident layers "
+                         "(score -> on-device head budgets -> select -> compact -> attend per layer), eagerly and "
+                         "as one HIP graph; 0 skips it")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="before the warm-up, copy 256 MiB device-to-device three times: a kernel of known traffic "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
@@ -272,6 +346,8 @@ def main():
                          "peak_GBs": HBM_PEAK_GBS},
         },
     }
+    if args.stack_layers > 0:
+        out["stack"] = layer_stack(torch, mk, cfg, desc, args.stack_layers, layers, stride)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_oracle_baseline(cfg)
     print(json.dumps(out))
