@@ -164,6 +164,34 @@ def layer_stack(torch, mk, cfg, desc, n_layers, have, stride):
             "kept_rows_per_layer_min_max": [min(kept), max(kept)], "capacity_per_layer": cap}
 
 
+def layer_importance_rate(torch, mk, n_tokens, hidden=4096):
+    """Layer-importance reduction over [n_tokens, hidden] bf16 hidden states (LLaDA-8B's width): HBM-bound."""
+    sets = []
+    for i in range(2):  # two input sets (1.1 GB), so that no call finds its rows in a cache
+        g = torch.Generator(device="cuda")
+        g.manual_seed(900 + i)
+        a = torch.randn((n_tokens, hidden), generator=g, device="cuda", dtype=torch.float32)
+        b = a + 0.5 * torch.randn((n_tokens, hidden), generator=g, device="cuda", dtype=torch.float32)
+        sets.append((a.to(torch.bfloat16), b.to(torch.bfloat16)))
+        del a, b
+    out = torch.empty(1, dtype=torch.float32, device="cuda")
+    ws = torch.empty(mk.maskkv_layer_importance_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    for i in range(4):
+        mk.maskkv_layer_importance(sets[i % 2][0], sets[i % 2][1], out, ws)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 16
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(reps):
+        mk.maskkv_layer_importance(sets[i % 2][0], sets[i % 2][1], out, ws)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    nbytes = 2.0 * n_tokens * hidden * 2
+    return {"n_tokens": n_tokens, "hidden": hidden, "ms": ms, "bound": "hbm", "achieved_GBs": nbytes / (ms * 1e-3) / 1e9,
+            "peak_GBs": HBM_PEAK_GBS, "frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "importance": float(out.item())}
+
+
 def cpu_oracle_baseline(cfg, budget_seconds=15.0):
     """Time the float64 oracle (score+pool+select+compact+attend) head by head on the host cores."""
     import torch
@@ -348,6 +376,7 @@ def main():
     }
     if args.stack_layers > 0:
         out["stack"] = layer_stack(torch, mk, cfg, desc, args.stack_layers, layers, stride)
+        out["layer_importance"] = layer_importance_rate(torch, mk, N)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_oracle_baseline(cfg)
     print(json.dumps(out))

@@ -17,6 +17,9 @@
  *                   eviction removes; used for the speed-up figure).
  *   maskkv_head_budgets  Stage 2, head level: prompt preference P_h and
  *                   k_{l,h} = floor(alpha k_l + (1-alpha) N_h k_l P_h / sum_j P_j).
+ *   maskkv_layer_importance, maskkv_layer_budgets   Stage 2, layer level: I^(l) = 1 - mean
+ *                   cosine similarity of the attention sub-layer's input and output states, and
+ *                   the boundary-aware split of the total budget over the layers.
  *
  * Conventions
  *  - Every pointer marked DEVICE must be device memory reachable from the current HIP
@@ -195,6 +198,33 @@ int maskkv_attend_full(const maskkv_desc* desc, const maskkv_tensor* Q_resp,
  */
 int maskkv_head_budgets(const maskkv_desc* desc, const float* prompt_mass, int32_t k_l, float alpha,
                         int32_t* budgets, void* stream);
+
+/* Workspace (DEVICE bytes) needed by maskkv_layer_importance.  256-byte alignment. */
+int maskkv_layer_importance_workspace_bytes(size_t* bytes);
+
+/*
+ * Stage 2, layer level, the layer importance metric:
+ *   importance[0] = 1 - (1/n) sum_i cos_sim(h_in[i, :], h_out[i, :])
+ * over the n_tokens rows of a layer's attention sub-layer input and output hidden states.
+ * h_in, h_out: DEVICE [n_tokens, hidden] in `dtype` (a maskkv_dtype), rows row_stride elements apart
+ * (row_stride >= hidden), pointers and row stride multiples of 16 bytes, hidden a multiple of 8
+ * elements.  importance: DEVICE float [1].  fp32 accumulation.  n_tokens >= 1.
+ */
+int maskkv_layer_importance(const void* h_in, const void* h_out, int64_t n_tokens, int32_t hidden, int32_t dtype,
+                            int64_t row_stride, float* importance, void* workspace, size_t workspace_bytes,
+                            void* stream);
+
+/*
+ * Stage 2, layer level, the boundary-aware budget allocation (host arithmetic, no device work):
+ *   k_base = floor(beta * k_p / L),  k_imp = k_p - L * k_base;
+ *   k_imp is split between the boundary layers and the other (middle) layers in proportion to the sums
+ *   of their importances; every layer receives k_base plus the floor of an equal share of its group's part.
+ * importance: HOST float [n_layers]; boundary: HOST int32 [n_boundary] layer numbers, or NULL for
+ * {first, last}; k_l: HOST int64 [n_layers] output.  k_p >= 0, 0 <= beta <= 1, importances >= 0 with a
+ * positive sum.  The budget lost to the floors is left unallocated (sum k_l <= k_p).
+ */
+int maskkv_layer_budgets(const float* importance, int32_t n_layers, int64_t k_p, float beta,
+                         const int32_t* boundary, int32_t n_boundary, int64_t* k_l);
 
 #ifdef __cplusplus
 }

@@ -29,6 +29,7 @@ SYMBOLS = [
     "maskkv_compact",
     "maskkv_attend_workspace_bytes", "maskkv_attend", "maskkv_attend_full",
     "maskkv_head_budgets",
+    "maskkv_layer_importance_workspace_bytes", "maskkv_layer_importance", "maskkv_layer_budgets",
 ]
 
 
@@ -212,6 +213,39 @@ def maskkv_head_budgets(desc: Desc, prompt_mass: torch.Tensor, k_l: int, alpha: 
                         stream=None) -> None:
     _check(_lib.maskkv_head_budgets(ct.byref(desc.c()), _ptr(prompt_mass), ct.c_int32(k_l), ct.c_float(alpha),
                                     _ptr(budgets), _stream(stream)), "maskkv_head_budgets")
+
+
+def maskkv_layer_importance_workspace_bytes() -> int:
+    n = ct.c_size_t(0)
+    _check(_lib.maskkv_layer_importance_workspace_bytes(ct.byref(n)), "maskkv_layer_importance_workspace_bytes")
+    return int(n.value)
+
+
+def maskkv_layer_importance(h_in: torch.Tensor, h_out: torch.Tensor, importance: torch.Tensor,
+                            workspace: Optional[torch.Tensor], stream=None) -> None:
+    """h_in, h_out: [n_tokens, hidden] device tensors of the same dtype and row stride; importance: float32 [1]."""
+    assert h_in.is_cuda and h_in.dim() == 2 and h_in.stride(1) == 1 and h_out.shape == h_in.shape
+    assert h_out.stride() == h_in.stride() and h_out.dtype == h_in.dtype
+    wp, wn = _ws(workspace)
+    _check(_lib.maskkv_layer_importance(_ptr(h_in), _ptr(h_out), ct.c_int64(h_in.shape[0]), ct.c_int32(h_in.shape[1]),
+                                        ct.c_int32(_dtype_code(h_in)), ct.c_int64(h_in.stride(0)), _ptr(importance),
+                                        wp, wn, _stream(stream)), "maskkv_layer_importance")
+
+
+def maskkv_layer_budgets(importance: Sequence[float], k_p: int, beta: float,
+                         boundary: Optional[Sequence[int]] = None) -> list:
+    """Host arithmetic: per-layer budgets k_l from the layer importances."""
+    n = len(importance)
+    imp = (ct.c_float * n)(*[float(x) for x in importance])
+    out = (ct.c_int64 * n)()
+    if boundary is None:
+        bptr, nb = None, 0
+    else:
+        barr = (ct.c_int32 * len(boundary))(*[int(x) for x in boundary])
+        bptr, nb = barr, len(boundary)
+    _check(_lib.maskkv_layer_budgets(imp, ct.c_int32(n), ct.c_int64(int(k_p)), ct.c_float(beta), bptr, ct.c_int32(nb),
+                                     out), "maskkv_layer_budgets")
+    return [int(x) for x in out]
 
 
 def raw_library() -> ct.CDLL:

@@ -295,4 +295,86 @@ int maskkv_head_budgets(const maskkv_desc* desc, const float* prompt_mass, int32
   return launch_head_budgets(desc, prompt_mass, k_l, alpha, budgets, reinterpret_cast<hipStream_t>(stream));
 }
 
+int maskkv_layer_importance_workspace_bytes(size_t* bytes) {
+  if (!bytes) {
+    set_error("bytes is NULL");
+    return MASKKV_EINVAL;
+  }
+  *bytes = layer_importance_workspace_bytes();
+  return MASKKV_OK;
+}
+
+int maskkv_layer_importance(const void* h_in, const void* h_out, int64_t n_tokens, int32_t hidden, int32_t dtype,
+                            int64_t row_stride, float* importance, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+  if (dtype != MASKKV_F32 && dtype != MASKKV_BF16) {
+    set_error("dtype %d is neither MASKKV_F32 nor MASKKV_BF16", dtype);
+    return MASKKV_EDTYPE;
+  }
+  const int64_t eb = dtype == MASKKV_BF16 ? 2 : 4;
+  if (!h_in || !h_out || !importance || n_tokens < 1 || hidden < 8 || (hidden & 7) || row_stride < hidden) {
+    set_error("layer_importance: NULL pointer, n_tokens %lld < 1, hidden %d not a positive multiple of 8, or "
+              "row_stride %lld < hidden", (long long)n_tokens, hidden, (long long)row_stride);
+    return MASKKV_EINVAL;
+  }
+  if (((uintptr_t)h_in & 15) || ((uintptr_t)h_out & 15) || ((row_stride * eb) & 15) || ((hidden * eb) & 15)) {
+    set_error("layer_importance: pointers, rows and row stride must be multiples of 16 bytes");
+    return MASKKV_EINVAL;
+  }
+  if (int e = check_workspace("layer_importance", workspace, workspace_bytes, layer_importance_workspace_bytes()))
+    return e;
+  return launch_layer_importance(h_in, h_out, n_tokens, hidden, dtype, row_stride * eb, importance, workspace,
+                                 reinterpret_cast<hipStream_t>(stream));
+}
+
+int maskkv_layer_budgets(const float* importance, int32_t n_layers, int64_t k_p, float beta, const int32_t* boundary,
+                         int32_t n_boundary, int64_t* k_l) {
+  if (!importance || !k_l || n_layers < 1 || k_p < 0 || !(beta >= 0.f && beta <= 1.f) || n_boundary < 0 ||
+      (n_boundary > 0 && !boundary)) {
+    set_error("layer_budgets: NULL pointer, n_layers %d < 1, k_p %lld < 0, beta %g outside [0, 1] or bad boundary list",
+              n_layers, (long long)k_p, (double)beta);
+    return MASKKV_EINVAL;
+  }
+  // group membership: 1 = boundary
+  int first_last[2] = {0, n_layers - 1};
+  const int32_t* bl = boundary ? boundary : first_last;
+  const int nbl = boundary ? n_boundary : (n_layers > 1 ? 2 : 1);
+  int n_b = 0;
+  double imp_b = 0.0, imp_m = 0.0;
+  for (int l = 0; l < n_layers; ++l) {
+    if (!(importance[l] >= 0.f)) {
+      set_error("layer_budgets: importance[%d] = %g is negative or NaN", l, (double)importance[l]);
+      return MASKKV_EINVAL;
+    }
+    bool is_b = false;
+    for (int i = 0; i < nbl; ++i) {
+      if (bl[i] < 0 || bl[i] >= n_layers) {
+        set_error("layer_budgets: boundary layer %d outside 0..%d", bl[i], n_layers - 1);
+        return MASKKV_EINVAL;
+      }
+      is_b = is_b || bl[i] == l;
+    }
+    if (is_b) {
+      ++n_b;
+      imp_b += (double)importance[l];
+    } else {
+      imp_m += (double)importance[l];
+    }
+    k_l[l] = is_b ? 1 : 0;  // remembered until the shares are known
+  }
+  if (!(imp_b + imp_m > 0.0)) {
+    set_error("layer_budgets: the importances sum to zero");
+    return MASKKV_EINVAL;
+  }
+  const int n_m = n_layers - n_b;
+  const int64_t k_base = (int64_t)floor((double)beta * (double)k_p / (double)n_layers);
+  const double k_imp = (double)(k_p - (int64_t)n_layers * k_base);
+  const double part_b = k_imp * imp_b / (imp_b + imp_m);
+  const double part_m = k_imp - part_b;
+  const int64_t share_b = n_b > 0 ? (int64_t)floor(part_b / n_b) : 0;
+  const int64_t share_m = n_m > 0 ? (int64_t)floor(part_m / n_m) : 0;
+  for (int l = 0; l < n_layers; ++l) k_l[l] = k_base + (k_l[l] ? share_b : share_m);
+  return MASKKV_OK;
+}
+
 }  // extern "C"

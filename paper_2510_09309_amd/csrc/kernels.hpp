@@ -29,4 +29,9 @@ int launch_attend(const maskkv_desc* d, const Lens& lens, bool full, const View&
                   const int32_t* cu_budget, int64_t capacity, const View& K2, const View& V2, float scale,
                   const View& O, float* lse, void* workspace, hipStream_t stream);
 
+// layer.hip
+size_t layer_importance_workspace_bytes();
+int launch_layer_importance(const void* h_in, const void* h_out, int64_t n, int hidden, int dtype, int64_t row_bytes,
+                            float* importance, void* workspace, hipStream_t stream);
+
 }  // namespace maskkv

@@ -106,6 +106,18 @@ def make_response_step(seed: int, H: int, d: int, n_m: int, dtype: str = "bf16",
     return tuple(out)
 
 
+def make_hidden_states(seed: int, n: int, hidden: int, dtype: str, drift: float):
+    """Stand-ins for an attention sub-layer's input and output hidden states [n, hidden]: Gaussian rows, the
+    output being the input plus `drift` times fresh Gaussian noise (so the rows' cosine similarity is about
+    1/sqrt(1 + drift^2)); rounded to the storage dtype.  Returns float32 arrays holding the rounded values."""
+    rng = np.random.default_rng(seed)
+    h_in = rng.standard_normal((n, hidden)).astype(np.float32)
+    h_out = h_in + np.float32(drift) * rng.standard_normal((n, hidden)).astype(np.float32)
+    if dtype == "bf16":
+        return round_to_bf16(h_in), round_to_bf16(h_out)
+    return h_in, h_out
+
+
 def budgets_two_level(H: int, avg: int, seed: int, ratio: int = 2) -> np.ndarray:
     """Per-head integer budgets summing to H*avg: half the heads (seeded choice) get ``ratio`` x the others.
 

@@ -4,6 +4,8 @@ import ctypes as ct
 import os
 import re
 
+import numpy as np
+
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -100,3 +102,30 @@ def test_bad_call_arguments_are_rejected_before_launch(mk):
     assert lib.maskkv_head_budgets(ct.byref(desc), f, ct.c_int32(10), ct.c_float(1.5), f, None) == 1
     assert lib.maskkv_head_budgets(ct.byref(desc), f, ct.c_int32(-1), ct.c_float(0.1), f, None) == 1
     assert b"alpha" in lib.maskkv_last_error()
+
+
+def test_layer_budgets_host_arithmetic_matches_the_oracle(mk):
+    """maskkv_layer_budgets is host-only arithmetic: compare with the oracle on the same float32 importances."""
+    from oracle import maskkv_oracle as orc
+    rng = np.random.default_rng(11)
+    cases = [(32, 32 * 256, 0.4, None), (32, 8192, 0.4, [0, 31]), (12, 1000, 0.25, [0, 1, 11]), (1, 77, 0.4, None),
+             (5, 0, 0.4, None), (7, 12345, 1.0, None), (7, 12345, 0.0, [3])]
+    for L, k_p, beta, boundary in cases:
+        imp = rng.random(L).astype(np.float32) + np.float32(0.01)
+        got = mk.maskkv_layer_budgets(imp, k_p, beta, boundary)
+        want = orc.layer_budgets(imp.astype(np.float64), k_p, np.float64(np.float32(beta)), boundary)
+        assert got == want.tolist(), (L, k_p, beta, boundary)
+        assert sum(got) <= k_p
+    # the worked case pinned for the oracle (exact binary factors): L=4, k_p=400, beta=0.5, importances 1,2,3,2
+    assert mk.maskkv_layer_budgets([1.0, 2.0, 3.0, 2.0], 400, 0.5) == orc.layer_budgets(
+        np.array([1.0, 2.0, 3.0, 2.0]), 400, 0.5).tolist()
+    with pytest.raises(mk.MaskKVError):
+        mk.maskkv_layer_budgets([0.0, 0.0], 10, 0.4)
+    with pytest.raises(mk.MaskKVError):
+        mk.maskkv_layer_budgets([1.0, 1.0], 10, 0.4, [5])
+    lib = mk.raw_library()
+    f = ct.c_void_p(0x1000)
+    assert lib.maskkv_layer_importance(f, f, ct.c_int64(10), ct.c_int32(100), ct.c_int32(1), ct.c_int64(100), f, f,
+                                       ct.c_size_t(1 << 20), None) == 1     # hidden not a multiple of 8
+    assert lib.maskkv_layer_importance(f, f, ct.c_int64(10), ct.c_int32(128), ct.c_int32(1), ct.c_int64(128), f, None,
+                                       ct.c_size_t(0), None) == 4           # no workspace

@@ -1,0 +1,67 @@
+"""Layer importance kernel against the float64 oracle (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import maskkv_oracle as orc
+from paper_2510_09309_amd import synth
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+
+# fp32 accumulation of `hidden` products and of n cosines against float64: a few ulp of fp32 on values <= 1
+IMPORTANCE_ATOL = 5e-6
+
+
+def gpu_importance(h_in: np.ndarray, h_out: np.ndarray, dtype: str, row_stride=None) -> float:
+    m = hp.mk()
+    n, hidden = h_in.shape
+    stride = hidden if row_stride is None else row_stride
+    tdt = hp.torch_dtype(dtype)
+    a = torch.zeros((n, stride), dtype=tdt, device="cuda")
+    b = torch.full((n, stride), 7.0, dtype=tdt, device="cuda")   # padding columns must never be read
+    a[:, :hidden] = torch.from_numpy(h_in).to("cuda").to(tdt)
+    b[:, :hidden] = torch.from_numpy(h_out).to("cuda").to(tdt)
+    out = torch.full((1,), float("nan"), dtype=torch.float32, device="cuda")
+    ws = hp.workspace(m.maskkv_layer_importance_workspace_bytes())
+    m.maskkv_layer_importance(a[:, :hidden], b[:, :hidden], out, ws)
+    torch.cuda.synchronize()
+    return float(out.item())
+
+
+@pytest.mark.parametrize("n,hidden,dtype,drift,stride", [
+    (1000, 4096, "bf16", 0.5, None),    # the model's hidden size, several rows per wave
+    (37, 512, "f32", 2.0, 520),         # ragged rows per wave, padded row stride
+    (1, 4096, "bf16", 1.0, None),       # a single token
+    (9001, 1024, "bf16", 0.1, 1032),    # more rows than waves in the grid
+    (300, 8, "f32", 1.0, None),         # shortest legal row: most lanes idle
+])
+def test_layer_importance_matches_oracle(n, hidden, dtype, drift, stride):
+    h_in, h_out = synth.make_hidden_states(500 + n, n, hidden, dtype, drift)
+    want = orc.layer_importance(h_in, h_out)
+    got = gpu_importance(h_in, h_out, dtype, stride)
+    assert abs(got - want) <= IMPORTANCE_ATOL, (got, want)
+
+
+def test_layer_importance_special_cases():
+    h_in, _ = synth.make_hidden_states(1, 64, 256, "f32", 0.0)
+    assert abs(gpu_importance(h_in, h_in, "f32")) <= IMPORTANCE_ATOL               # identical states: 0
+    assert abs(gpu_importance(h_in, -h_in, "f32") - 2.0) <= IMPORTANCE_ATOL        # opposite states: 2
+    assert abs(gpu_importance(h_in, 3.0 * h_in, "f32")) <= IMPORTANCE_ATOL         # scale invariance
+
+
+def test_importance_feeds_layer_budgets():
+    """Importances measured on the device, budgets from the host formula, both against the oracle."""
+    m = hp.mk()
+    drifts = [1.5, 0.2, 0.3, 0.25, 0.4, 1.0]
+    imps, refs = [], []
+    for l, dr in enumerate(drifts):
+        h_in, h_out = synth.make_hidden_states(700 + l, 257, 1024, "bf16", dr)
+        imps.append(gpu_importance(h_in, h_out, "bf16"))
+        refs.append(orc.layer_importance(h_in, h_out))
+    assert np.abs(np.array(imps) - np.array(refs)).max() <= IMPORTANCE_ATOL
+    k_p = 6 * 256
+    got = m.maskkv_layer_budgets(imps, k_p, 0.4)
+    want = orc.layer_budgets(np.array(imps, dtype=np.float32).astype(np.float64), k_p, np.float64(np.float32(0.4)))
+    assert got == want.tolist() and sum(got) <= k_p
+    assert got[0] > got[1] and got[-1] > got[2]   # the drifting boundary layers receive more
