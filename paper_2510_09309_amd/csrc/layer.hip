@@ -16,6 +16,7 @@ namespace {
 constexpr int kImpThreads = 256;
 constexpr int kImpWaves = kImpThreads / 64;
 constexpr int kImpGroups = 2048;  // eight resident workgroups per compute unit
+constexpr int kImpUnroll = 8;
 
 struct ImportanceParams {
   const char* h_in;
@@ -64,19 +65,19 @@ __global__ __launch_bounds__(kImpThreads) void importance_kernel(const Importanc
     const char* b = prm.h_out + row * prm.row_bytes;
     float dot = 0.f, na = 0.f, nb = 0.f;
     int p = lane;
-    for (; p + 3 * 64 < pieces; p += 4 * 64) {  // eight independent 16-byte loads in flight per lane
-      u32x4 va[4], vb[4];
+    for (; p + (kImpUnroll - 1) * 64 < pieces; p += kImpUnroll * 64) {  // 2 * kImpUnroll independent 16-byte loads
+      u32x4 va[kImpUnroll], vb[kImpUnroll];                             // in flight per lane; the data is read once
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        va[u] = *reinterpret_cast<const u32x4*>(a + (int64_t)(p + u * 64) * 16);
-        vb[u] = *reinterpret_cast<const u32x4*>(b + (int64_t)(p + u * 64) * 16);
+      for (int u = 0; u < kImpUnroll; ++u) {
+        va[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(a + (int64_t)(p + u * 64) * 16));
+        vb[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(b + (int64_t)(p + u * 64) * 16));
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) accumulate<T>(va[u], vb[u], dot, na, nb);
+      for (int u = 0; u < kImpUnroll; ++u) accumulate<T>(va[u], vb[u], dot, na, nb);
     }
     for (; p < pieces; p += 64)
-      accumulate<T>(*reinterpret_cast<const u32x4*>(a + (int64_t)p * 16),
-                    *reinterpret_cast<const u32x4*>(b + (int64_t)p * 16), dot, na, nb);
+      accumulate<T>(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(a + (int64_t)p * 16)),
+                    __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(b + (int64_t)p * 16)), dot, na, nb);
     dot = wave_sum(dot);
     na = wave_sum(na);
     nb = wave_sum(nb);
