@@ -502,30 +502,43 @@ __global__ __launch_bounds__(kAttThreads) void attend_narrow_kernel(const Attend
   if (prm.lse && wave == 0 && g == 0) prm.lse[(int64_t)bh * prm.n_resp + q] = (M + __log2f(L)) * kLn2;
 }
 
-// Merge the key splits of one query row: O = sum_s w_s O_s / sum_s w_s l_s, w_s = 2^(m_s - max m).
+// Merge the key splits of the query rows: O = sum_s w_s O_s / sum_s w_s l_s, w_s = 2^(m_s - max m).
+// A row is served by D/4 consecutive threads (four output elements each, 16-byte loads of the partials).
 template <typename T, int D>
-__global__ __launch_bounds__(D) void attend_merge_kernel(const AttendParams prm) {
-  const int q = blockIdx.x;
+__global__ __launch_bounds__(256) void attend_merge_kernel(const AttendParams prm) {
+  constexpr int kTPR = D / 4;          // threads per row
+  constexpr int kRows = 256 / kTPR;    // rows per workgroup
   const int bh = blockIdx.y;
   const int b = bh / prm.H, h = bh % prm.H;
-  const int e = threadIdx.x;
+  const int q = blockIdx.x * kRows + (int)threadIdx.x / kTPR;
+  const int e = ((int)threadIdx.x % kTPR) * 4;
+  if (q >= prm.n_resp) return;
   float M = kNegBig;
   for (int s = 0; s < prm.n_splits; ++s)
     M = fmaxf(M, prm.part_ml[((int64_t)bh * prm.n_splits + s) * prm.n_resp + q].x);
-  float L = 0.f, acc = 0.f;
+  float L = 0.f;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int s = 0; s < prm.n_splits; ++s) {
     const int64_t slot = ((int64_t)bh * prm.n_splits + s) * prm.n_resp + q;
     const float2 ml = prm.part_ml[slot];
     const float w = fast_exp2(ml.x - M);
+    const float4 v = *reinterpret_cast<const float4*>(prm.part_o + slot * D + e);
     L += w * ml.y;
-    acc += w * prm.part_o[slot * D + e];
+    acc.x += w * v.x;
+    acc.y += w * v.y;
+    acc.z += w * v.z;
+    acc.w += w * v.w;
   }
-  const float v = acc / L;
+  const float inv = 1.f / L;
   char* orow = prm.O.row(b, h, q);
-  if (sizeof(T) == 2)
-    reinterpret_cast<uint16_t*>(orow)[e] = (uint16_t)f32_to_bf16_rne(v);
-  else
-    reinterpret_cast<float*>(orow)[e] = v;
+  if (sizeof(T) == 2) {
+    u32x2 w;
+    w[0] = pack_bf16x2(acc.x * inv, acc.y * inv);
+    w[1] = pack_bf16x2(acc.z * inv, acc.w * inv);
+    *reinterpret_cast<u32x2*>(orow + e * 2) = w;
+  } else {
+    *reinterpret_cast<float4*>(orow + e * 4) = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+  }
   if (prm.lse && e == 0) prm.lse[(int64_t)bh * prm.n_resp + q] = (M + __log2f(L)) * kLn2;
 }
 
@@ -533,7 +546,7 @@ int attend_splits(const maskkv_desc* d, bool full) {
   if (!full) return 1;
   const int64_t qtiles = (d->n_resp + kQPerBlock - 1) / kQPerBlock;
   const int64_t blocks = qtiles * d->B * d->H;
-  int64_t s = (1024 + blocks - 1) / blocks;
+  int64_t s = (512 + blocks - 1) / blocks;  // about two workgroups per compute unit (measured best)
   const int64_t by_len = ((int64_t)d->P_max + d->n_resp + 511) / 512;
   if (s > by_len) s = by_len;
   if (s > 64) s = 64;
@@ -574,7 +587,9 @@ int launch_attend_t(const AttendParams& prm, int B, hipStream_t stream) {
   hipLaunchKernelGGL((attend_kernel<T, D>), grid, dim3(kAttThreads), 0, stream, prm);
   if (int e = check_launch("attend")) return e;
   if (prm.n_splits > 1) {
-    hipLaunchKernelGGL((attend_merge_kernel<T, D>), dim3(prm.n_resp, B * prm.H), dim3(D), 0, stream, prm);
+    constexpr int kRows = 256 / (D / 4);
+    hipLaunchKernelGGL((attend_merge_kernel<T, D>), dim3((prm.n_resp + kRows - 1) / kRows, B * prm.H), dim3(256), 0,
+                       stream, prm);
     return check_launch("attend merge");
   }
   return MASKKV_OK;
