@@ -14,6 +14,12 @@ from the MaskKV paper (arXiv 2510.09309), Section 3.3 "The MaskKV Framework":
     response span over [kept prompt KV ; response KV].
   * Stage 2, head level: prompt preference ``P_h`` and the head budget formula
     ``k_{l,h}``; layer level: ``k_base``, ``k_imp``, group budgets and ``k_l``.
+  * Variants: grouped-query heads (Dream-7B, Section 4.1, shares one KV head between
+    several query heads; the paper does not say how votes map to a shared KV head, and
+    this oracle lets every mask query of every query head in the group vote), and the
+    response-token refresh criterion of the dLLM-Cache background (Section 3.1,
+    ``S_shift``: cosine similarity of a token's value vector between two steps below
+    a threshold).
 
 Everything is float64 numpy on one head at a time, with no blocking, fusion or
 reordering; a reader can check each function against the paper by eye.  It is only
@@ -50,6 +56,9 @@ __all__ = [
     "layer_importance",
     "layer_budgets",
     "kv_cache_bytes",
+    "score_grouped",
+    "attend_grouped",
+    "value_shift",
 ]
 
 
@@ -261,3 +270,49 @@ def layer_budgets(importance: np.ndarray, k_p: int, beta: float = 0.4, boundary=
 def kv_cache_bytes(seq_len: int, n_heads: int, d_head: int, elem_bytes: int = 2) -> int:
     """Mem_KV = 2 * L * H * d_head * s_bf16 bytes per layer (appendix, evaluation metrics)."""
     return 2 * seq_len * n_heads * d_head * elem_bytes
+
+
+def score_grouped(Q_heads: np.ndarray, K_full: np.ndarray, n_prompt: int, scale: float | None = None):
+    """Mask-Voting for ONE key/value head shared by g query heads (grouped-query attention).
+
+    Q_heads: [g, n_m, d] mask queries of the g query heads that read this KV head;
+    K_full: [N, d].  Every mask query of every head in the group votes:
+      I[j] = sum_{h in group} sum_i A^(h)_ij,   mass = sum_{j < n_prompt} I[j].
+    The paper evaluates a grouped-query model (Dream-7B) without stating this mapping;
+    the plain sum is the reading taken here (it is Stage 1's sum over "all mask
+    queries", with the queries of one KV head's group being all of its queries).
+    """
+    Q_heads = _f64(Q_heads)
+    assert Q_heads.ndim == 3
+    I = np.zeros(n_prompt, dtype=np.float64)
+    for g in range(Q_heads.shape[0]):
+        I_g, _ = score(Q_heads[g], K_full, n_prompt, scale)
+        I = I + I_g
+    return I, float(I.sum())
+
+
+def attend_grouped(Q_heads, Kc, Vc, K_resp, V_resp, scale: float | None = None):
+    """Attention of the g query heads of one group over their shared evicted cache.
+
+    Q_heads: [g, n_r, d]; the cache and the response rows belong to the group's single KV
+    head.  Returns O [g, n_r, d]: every query head attends on its own (Section 3.1's layer
+    forward equation per head), only the keys and values are shared.
+    """
+    Q_heads = _f64(Q_heads)
+    return np.stack([attend(Q_heads[g], Kc, Vc, K_resp, V_resp, scale) for g in range(Q_heads.shape[0])])
+
+
+def value_shift(V_now: np.ndarray, V_prev: np.ndarray, delta: float):
+    """Response tokens whose value vector moved between two denoising steps (Section 3.1, S_shift).
+
+    V_now, V_prev: [n, width] value features of the n response tokens at steps t and t-1.
+    Returns (cos, refresh): cos[i] = cos_sim(V_now[i], V_prev[i]); refresh = ascending int32
+    positions i with cos[i] < delta (the tokens dLLM-Cache recomputes at this step in
+    addition to the periodic refresh).
+    """
+    a = _f64(V_now)
+    b = _f64(V_prev)
+    assert a.shape == b.shape and a.ndim == 2
+    cos = (a * b).sum(axis=1) / (np.linalg.norm(a, axis=1) * np.linalg.norm(b, axis=1))
+    refresh = np.nonzero(cos < delta)[0].astype(np.int32)
+    return cos, refresh

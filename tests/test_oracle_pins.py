@@ -421,3 +421,83 @@ def test_kv_cache_bytes_formula():
         rows = [ln.split() for ln in f if ln.strip() and not ln.startswith("#")]
     for L, H, d, expect in rows:
         assert orc.kv_cache_bytes(int(L), int(H), int(d)) == int(expect)
+
+
+# --------------------------------------------------------------------------- variants: grouped queries, value shift
+def test_grouped_score_is_the_vote_of_all_stacked_queries():
+    """Summing the votes of the g query heads equals voting with their queries stacked: brute force."""
+    rng = np.random.default_rng(23)
+    g, n_m, d, P, N = 3, 4, 6, 9, 13
+    Q = rng.standard_normal((g, n_m, d))
+    K = rng.standard_normal((N, d))
+    I, mass = orc.score_grouped(Q, K, P)
+    stacked = brute_scores(Q.reshape(g * n_m, d).tolist(), K.tolist(), P, 1.0 / math.sqrt(d))
+    np.testing.assert_allclose(I, stacked, rtol=1e-12)
+    assert math.isclose(mass, sum(stacked), rel_tol=1e-12)
+    # a group of one is plain multi-head scoring
+    I1, _ = orc.score_grouped(Q[:1], K, P)
+    np.testing.assert_allclose(I1, orc.score(Q[0], K, P)[0], rtol=0, atol=0)
+    # all N columns together hold the whole attention mass of the g*n_m voting rows
+    I_all, _ = orc.score_grouped(Q, K, N)
+    assert math.isclose(I_all.sum(), g * n_m, rel_tol=1e-12)
+
+
+def test_grouped_score_keeps_heads_apart_from_each_other():
+    """A head whose queries are zero votes uniformly; it must not leak into the other head's softmax."""
+    rng = np.random.default_rng(29)
+    n_m, d, P, N = 3, 4, 7, 10
+    Qa = rng.standard_normal((n_m, d))
+    K = rng.standard_normal((N, d))
+    I, _ = orc.score_grouped(np.stack([Qa, np.zeros((n_m, d))]), K, P)
+    np.testing.assert_allclose(I - n_m / N, orc.score(Qa, K, P)[0], rtol=1e-12)
+
+
+def test_grouped_attention_shares_only_keys_and_values():
+    rng = np.random.default_rng(31)
+    g, n_r, d, k = 2, 3, 4, 5
+    Q = rng.standard_normal((g, n_r, d))
+    Kc, Vc = rng.standard_normal((k, d)), rng.standard_normal((k, d))
+    Kr, Vr = rng.standard_normal((n_r, d)), rng.standard_normal((n_r, d))
+    O = orc.attend_grouped(Q, Kc, Vc, Kr, Vr)
+    assert O.shape == (g, n_r, d)
+    keys = np.concatenate([Kc, Kr]).tolist()
+    vals = np.concatenate([Vc, Vr]).tolist()
+    for h in range(g):
+        np.testing.assert_allclose(O[h], brute_attend(Q[h].tolist(), keys, vals, 1.0 / math.sqrt(d)), rtol=1e-12)
+
+
+def test_value_shift_closed_forms():
+    """Rows rotated by a known angle have cos = cos(angle); the refresh set is those below the threshold."""
+    angles = np.array([0.0, 0.1, 0.5, 1.0, math.pi / 2, 2.0, math.pi])
+    prev = np.stack([np.array([2.0, 0.0, 0.0]) for _ in angles])
+    now = np.stack([0.5 * np.array([math.cos(a), math.sin(a), 0.0]) for a in angles])  # length change is ignored
+    cos, refresh = orc.value_shift(now, prev, delta=0.9)
+    np.testing.assert_allclose(cos, np.cos(angles), atol=1e-15)
+    assert refresh.dtype == np.int32
+    assert refresh.tolist() == [2, 3, 4, 5, 6]          # cos(0.5) = 0.8776 < 0.9 <= cos(0.1) = 0.995
+    # strict inequality: a token exactly at the threshold is not refreshed
+    cos2, refresh2 = orc.value_shift(np.array([[1.0, 1.0]]), np.array([[1.0, 0.0]]), delta=0.0)
+    assert refresh2.tolist() == []
+    _, refresh3 = orc.value_shift(np.array([[0.0, 1.0]]), np.array([[1.0, 0.0]]), delta=0.0)
+    assert refresh3.tolist() == []
+    _, refresh4 = orc.value_shift(np.array([[-1.0, 1.0]]), np.array([[1.0, 0.0]]), delta=0.0)
+    assert refresh4.tolist() == [0]
+
+
+def test_value_shift_brute_force_and_symmetry():
+    rng = np.random.default_rng(37)
+    a = rng.standard_normal((12, 5))
+    b = a + 0.8 * rng.standard_normal((12, 5))
+    cos, refresh = orc.value_shift(a, b, delta=0.7)
+    for i in range(12):
+        dot = sum(a[i][t] * b[i][t] for t in range(5))
+        na = math.sqrt(sum(x * x for x in a[i]))
+        nb = math.sqrt(sum(x * x for x in b[i]))
+        assert math.isclose(cos[i], dot / (na * nb), rel_tol=1e-12)
+    assert refresh.tolist() == [i for i in range(12) if cos[i] < 0.7]
+    assert 0 < len(refresh) < 12                          # the case exercises both outcomes
+    cos_t, refresh_t = orc.value_shift(b, a, delta=0.7)   # symmetric in its two arguments
+    np.testing.assert_allclose(cos_t, cos, rtol=1e-15)
+    assert refresh_t.tolist() == refresh.tolist()
+    # the mean of the per-token similarities is what the layer importance metric averages
+    assert math.isclose(1.0 - cos.mean(), orc.layer_importance(a, b), rel_tol=1e-12)
