@@ -20,6 +20,8 @@
  *   maskkv_layer_importance, maskkv_layer_budgets   Stage 2, layer level: I^(l) = 1 - mean
  *                   cosine similarity of the attention sub-layer's input and output states, and
  *                   the boundary-aware split of the total budget over the layers.
+ *   maskkv_value_shift   Section 3.1 (feature-cache background): response tokens whose value
+ *                   vector turned by more than a threshold between two denoising steps.
  *
  * Conventions
  *  - Every pointer marked DEVICE must be device memory reachable from the current HIP
@@ -32,8 +34,14 @@
  *  - Every function returns a maskkv_status.  On any status other than MASKKV_OK nothing
  *    has been enqueued.  maskkv_last_error() gives a per-thread detail string.
  *  - Sequences: batch item b has P_b prompt tokens followed by n_resp response-span
- *    tokens (N_b = P_b + n_resp keys).  Heads are independent (MHA; one KV head per
- *    query head).
+ *    tokens (N_b = P_b + n_resp keys).  Key/value heads are independent.
+ *  - Grouped-query attention (the Dream-7B model of Section 4.1): desc->H counts KEY/VALUE
+ *    heads and desc->q_per_kv = g > 1 says that query heads h*g .. h*g+g-1 read KV head h.
+ *    Views of queries and outputs (Q_mask, Q_resp, O) then have H*g heads, lse has
+ *    B*H*g*n_resp entries, and everything per head (scores, prompt_mass, budgets, cu_budget,
+ *    the cache, K and V views) stays per KV head.  The paper does not say how votes map to a
+ *    shared KV head; here every mask query of every query head in the group votes
+ *    (scores = sum over the group of the per-head column sums).  g <= 64.
  */
 #ifndef MASKKV_H
 #define MASKKV_H
@@ -85,9 +93,11 @@ typedef struct maskkv_desc {
   int32_t d;        /* head_dim: 64 or 128 */
   int32_t dtype;    /* maskkv_dtype of Q, K, V, the cache and O */
   int32_t n_resp;   /* response-span length n_m: response keys per sequence; queries in attend */
-  int32_t n_query;  /* mask queries that vote in maskkv_score (normally n_resp; a sub-span is allowed) */
+  int32_t n_query;  /* mask queries per query head that vote in maskkv_score (normally n_resp; a sub-span,
+                       e.g. only the late response positions of the position-aware voting study, is
+                       expressed by pointing Q_mask at its first row) */
   int32_t P_max;    /* longest prompt in the batch */
-  int32_t reserved; /* must be 0 */
+  int32_t q_per_kv; /* grouped-query attention: query heads per key/value head; 0 or 1 = one each (MHA) */
   const int32_t* prompt_len; /* HOST [B] prompt lengths P_b in 0..P_max, or NULL: every P_b = P_max */
 } maskkv_desc;
 
@@ -110,9 +120,10 @@ int maskkv_score_workspace_bytes(const maskkv_desc* desc, size_t* bytes);
  * Stage 1, Mask-Voting.  For every (b, h):
  *   A = softmax over all N_b keys of (Q_mask[b,h] K_full[b,h]^T * scale)   (no mask)
  *   scores[(b*H + h)*score_stride + j] = sum_{i < n_query} A[i, j],  j in [0, P_b)
+ *                          (summed over the g query heads of the group too when q_per_kv = g > 1)
  *   prompt_mass[b*H + h] = sum_{j < P_b} scores[..j]   (the mask-to-prompt attention sum
  *                          S_{m->p} of the prompt-preference metric), if not NULL.
- * Q_mask: view [B, H, n_query, d].  K_full: view [B, H, N_b, d], prompt rows then
+ * Q_mask: view [B, H*g, n_query, d].  K_full: view [B, H, N_b, d], prompt rows then
  * response rows.  scale <= 0 selects 1/sqrt(d).  scores: DEVICE float, score_stride >=
  * P_max; entries j >= P_b are left untouched.  Accumulation is fp32 throughout.
  */
@@ -168,14 +179,15 @@ int maskkv_compact(const maskkv_desc* desc, const maskkv_tensor* K, const maskkv
 int maskkv_attend_workspace_bytes(const maskkv_desc* desc, int full, size_t* bytes);
 
 /*
- * Attention over the evicted cache.  For every (b, h) and response query i < n_resp:
- *   O[b,h,i,:] = sum_j softmax_j(Q_resp[b,h,i,:] . k_j * scale) v_j
+ * Attention over the evicted cache.  For every (b, h), query head hq of h's group (hq = h when
+ * q_per_kv <= 1) and response query i < n_resp:
+ *   O[b,hq,i,:] = sum_j softmax_j(Q_resp[b,hq,i,:] . k_j * scale) v_j
  * with j over the cache rows [cu_budget[bh], cu_budget[bh+1]) of Kc/Vc (DEVICE [capacity, d];
  * row numbers are clipped to capacity) followed by the n_resp rows of K_resp/V_resp (views
  * [B, H, n_resp, d]).  No mask.  lse (DEVICE float
- * [B*H*n_resp], optional) receives the natural-log softmax normaliser of every row.
+ * [B*H*g*n_resp], optional) receives the natural-log softmax normaliser of every row.
  * Inputs in desc->dtype, fp32 accumulation; probabilities are rounded to desc->dtype only
- * as the operand of the P.V product.  O: view [B, H, n_resp, d], written in desc->dtype.
+ * as the operand of the P.V product.  Q_resp, O: views [B, H*g, n_resp, d]; O is written in desc->dtype.
  */
 int maskkv_attend(const maskkv_desc* desc, const maskkv_tensor* Q_resp,
                   const void* Kc, const void* Vc, const int32_t* cu_budget, int64_t capacity,
@@ -191,7 +203,7 @@ int maskkv_attend_full(const maskkv_desc* desc, const maskkv_tensor* Q_resp,
 
 /*
  * Stage 2, head level, on the device.  For every b:
- *   P_h = prompt_mass[b*H+h] / n_query  (mask-to-prompt share of the mask rows' attention)
+ *   P_h = prompt_mass[b*H+h] / (g*n_query)  (mask-to-prompt share of the voting rows' attention)
  *   budgets[b*H+h] = floor(alpha*k_l + (1-alpha) * H * k_l * P_h / sum_h' P_h')
  * prompt_mass: DEVICE float [B*H] as written by maskkv_score; budgets: DEVICE int32 [B*H].
  * k_l is the layer's per-head average budget; 0 <= alpha <= 1.
@@ -225,6 +237,19 @@ int maskkv_layer_importance(const void* h_in, const void* h_out, int64_t n_token
  */
 int maskkv_layer_budgets(const float* importance, int32_t n_layers, int64_t k_p, float beta,
                          const int32_t* boundary, int32_t n_boundary, int64_t* k_l);
+
+/*
+ * Response-token refresh criterion of the feature-cache background (Section 3.1, the set S_shift):
+ *   cos[i]  = cos_sim(V_now[i, :], V_prev[i, :])  for the n_tokens response tokens of a layer
+ *   refresh = ascending positions i with cos[i] < delta (strict), count[0] of them.
+ * V_now, V_prev: DEVICE [n_tokens, width] in `dtype` (a maskkv_dtype; width = heads * head_dim), rows
+ * row_stride elements apart, pointers and row stride multiples of 16 bytes, width a multiple of 8.
+ * cos: DEVICE float [n_tokens]; refresh: DEVICE int32 [n_tokens] (entries >= count[0] untouched); count:
+ * DEVICE int32 [1].  fp32 accumulation; the comparison is made on the fp32 cosine.  A row of zeros has no
+ * cosine (NaN) and is not listed.  No workspace.
+ */
+int maskkv_value_shift(const void* V_now, const void* V_prev, int64_t n_tokens, int32_t width, int32_t dtype,
+                       int64_t row_stride, float delta, float* cos, int32_t* refresh, int32_t* count, void* stream);
 
 #ifdef __cplusplus
 }

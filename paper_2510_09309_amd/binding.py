@@ -30,6 +30,7 @@ SYMBOLS = [
     "maskkv_attend_workspace_bytes", "maskkv_attend", "maskkv_attend_full",
     "maskkv_head_budgets",
     "maskkv_layer_importance_workspace_bytes", "maskkv_layer_importance", "maskkv_layer_budgets",
+    "maskkv_value_shift",
 ]
 
 
@@ -46,7 +47,7 @@ class _CTensor(ct.Structure):
 
 class _CDesc(ct.Structure):
     _fields_ = [("B", ct.c_int32), ("H", ct.c_int32), ("d", ct.c_int32), ("dtype", ct.c_int32),
-                ("n_resp", ct.c_int32), ("n_query", ct.c_int32), ("P_max", ct.c_int32), ("reserved", ct.c_int32),
+                ("n_resp", ct.c_int32), ("n_query", ct.c_int32), ("P_max", ct.c_int32), ("q_per_kv", ct.c_int32),
                 ("prompt_len", ct.POINTER(ct.c_int32))]
 
 
@@ -77,10 +78,11 @@ class Desc:
     P_max: int
     n_query: Optional[int] = None
     prompt_len: Optional[Sequence[int]] = None
+    q_per_kv: int = 0   # query heads per key/value head (0 or 1: multi-head attention); H counts KV heads
 
     def c(self) -> _CDesc:
         nq = self.n_resp if self.n_query is None else self.n_query
-        c = _CDesc(self.B, self.H, self.d, self.dtype, self.n_resp, nq, self.P_max, 0, None)
+        c = _CDesc(self.B, self.H, self.d, self.dtype, self.n_resp, nq, self.P_max, int(self.q_per_kv), None)
         if self.prompt_len is not None:
             arr = (ct.c_int32 * len(self.prompt_len))(*[int(x) for x in self.prompt_len])
             c._keep = arr
@@ -246,6 +248,18 @@ def maskkv_layer_budgets(importance: Sequence[float], k_p: int, beta: float,
     _check(_lib.maskkv_layer_budgets(imp, ct.c_int32(n), ct.c_int64(int(k_p)), ct.c_float(beta), bptr, ct.c_int32(nb),
                                      out), "maskkv_layer_budgets")
     return [int(x) for x in out]
+
+
+def maskkv_value_shift(V_now: torch.Tensor, V_prev: torch.Tensor, delta: float, cos: torch.Tensor,
+                       refresh: torch.Tensor, count: torch.Tensor, stream=None) -> None:
+    """V_now, V_prev: [n_tokens, width] device tensors; cos: float32 [n]; refresh: int32 [n]; count: int32 [1]."""
+    assert V_now.is_cuda and V_now.dim() == 2 and V_now.stride(1) == 1 and V_prev.shape == V_now.shape
+    assert V_prev.stride() == V_now.stride() and V_prev.dtype == V_now.dtype
+    assert cos.dtype == torch.float32 and cos.numel() >= V_now.shape[0]
+    assert refresh.dtype == torch.int32 and refresh.numel() >= V_now.shape[0] and count.dtype == torch.int32
+    _check(_lib.maskkv_value_shift(_ptr(V_now), _ptr(V_prev), ct.c_int64(V_now.shape[0]), ct.c_int32(V_now.shape[1]),
+                                   ct.c_int32(_dtype_code(V_now)), ct.c_int64(V_now.stride(0)), ct.c_float(delta),
+                                   _ptr(cos), _ptr(refresh), _ptr(count), _stream(stream)), "maskkv_value_shift")
 
 
 def raw_library() -> ct.CDLL:

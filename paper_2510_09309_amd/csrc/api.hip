@@ -49,10 +49,15 @@ int check_desc(const maskkv_desc* d, Lens* lens) {
     set_error("H = %d (B*H = %lld) outside 1..65535", d->H, (long long)d->B * d->H);
     return MASKKV_ESHAPE;
   }
-  if (d->n_resp < 1 || d->n_query < 1 || d->P_max < 0 || d->reserved != 0) {
-    set_error("n_resp = %d, n_query = %d must be >= 1, P_max = %d >= 0, reserved = %d == 0", d->n_resp, d->n_query,
-              d->P_max, d->reserved);
+  if (d->n_resp < 1 || d->n_query < 1 || d->P_max < 0 || d->q_per_kv < 0 || d->q_per_kv > 64) {
+    set_error("n_resp = %d, n_query = %d must be >= 1, P_max = %d >= 0, q_per_kv = %d in 0..64", d->n_resp, d->n_query,
+              d->P_max, d->q_per_kv);
     return MASKKV_EINVAL;
+  }
+  if ((int64_t)d->n_query * query_heads_per_kv(d) > (1 << 20) || (int64_t)d->n_resp * query_heads_per_kv(d) > (1 << 20)) {
+    set_error("more than 2^20 query rows per key/value head (n_query %d, n_resp %d, q_per_kv %d)", d->n_query,
+              d->n_resp, d->q_per_kv);
+    return MASKKV_ESHAPE;
   }
   if ((int64_t)d->P_max + d->n_resp > (1 << 30)) {
     set_error("sequence length %lld too large", (long long)d->P_max + d->n_resp);
@@ -325,6 +330,27 @@ int maskkv_layer_importance(const void* h_in, const void* h_out, int64_t n_token
     return e;
   return launch_layer_importance(h_in, h_out, n_tokens, hidden, dtype, row_stride * eb, importance, workspace,
                                  reinterpret_cast<hipStream_t>(stream));
+}
+
+int maskkv_value_shift(const void* V_now, const void* V_prev, int64_t n_tokens, int32_t width, int32_t dtype,
+                       int64_t row_stride, float delta, float* cos, int32_t* refresh, int32_t* count, void* stream) {
+  if (dtype != MASKKV_F32 && dtype != MASKKV_BF16) {
+    set_error("dtype %d is neither MASKKV_F32 nor MASKKV_BF16", dtype);
+    return MASKKV_EDTYPE;
+  }
+  const int64_t eb = dtype == MASKKV_BF16 ? 2 : 4;
+  if (!V_now || !V_prev || !cos || !refresh || !count || n_tokens < 1 || n_tokens > 0x7FFFFFFF || width < 8 ||
+      (width & 7) || row_stride < width || !(delta == delta)) {
+    set_error("value_shift: NULL pointer, n_tokens %lld outside 1..2^31-1, width %d not a positive multiple of 8, "
+              "row_stride %lld < width, or delta is NaN", (long long)n_tokens, width, (long long)row_stride);
+    return MASKKV_EINVAL;
+  }
+  if (((uintptr_t)V_now & 15) || ((uintptr_t)V_prev & 15) || ((row_stride * eb) & 15)) {
+    set_error("value_shift: pointers and row stride must be multiples of 16 bytes");
+    return MASKKV_EINVAL;
+  }
+  return launch_value_shift(V_now, V_prev, n_tokens, width, dtype, row_stride * eb, delta, cos, refresh, count,
+                            reinterpret_cast<hipStream_t>(stream));
 }
 
 int maskkv_layer_budgets(const float* importance, int32_t n_layers, int64_t k_p, float beta, const int32_t* boundary,

@@ -40,10 +40,12 @@ struct AttendParams {
   const int32_t* cu;
   int64_t capacity;
   int H, BH, n_resp, full, n_splits;
+  int q_per_kv;  // query heads per key/value head
+  int n_q;       // query rows per key/value head = q_per_kv * n_resp
   float c;  // scale * log2(e)
   float* lse;
-  float* part_o;     // [BH][n_splits][n_resp][D]
-  float2* part_ml;   // [BH][n_splits][n_resp]
+  float* part_o;     // [BH][n_splits][n_q][D]
+  float2* part_ml;   // [BH][n_splits][n_q]
 };
 
 struct KeySpace {
@@ -159,8 +161,8 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const AttendParams 
   u32x4 qf[C::kSteps];
 #pragma unroll
   for (int s = 0; s < C::kSteps; ++s) {
-    if (q < prm.n_resp)
-      qf[s] = *reinterpret_cast<const u32x4*>(prm.Q.row(b, h, q) + s * 32 + g * 16);
+    if (q < prm.n_q)
+      qf[s] = *reinterpret_cast<const u32x4*>(prm.Q.group_row(b, h, prm.q_per_kv, prm.n_resp, q) + s * 32 + g * 16);
     else
       qf[s] = u32x4{0u, 0u, 0u, 0u};
   }
@@ -271,10 +273,10 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const AttendParams 
   }
 
   const float l_tot = l + xor32(l);
-  if (q >= prm.n_resp) return;
+  if (q >= prm.n_q) return;
   if (prm.n_splits == 1) {
     const float inv = 1.f / l_tot;
-    char* orow = prm.O.row(b, h, q);
+    char* orow = prm.O.group_row(b, h, prm.q_per_kv, prm.n_resp, q);
 #pragma unroll
     for (int db = 0; db < C::kDB; ++db)
 #pragma unroll
@@ -291,9 +293,9 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const AttendParams 
           *reinterpret_cast<float4*>(orow + e * 4) = make_float4(v0, v1, v2, v3);
         }
       }
-    if (prm.lse && g == 0) prm.lse[(int64_t)bh * prm.n_resp + q] = (m + __log2f(l_tot)) * kLn2;
+    if (prm.lse && g == 0) prm.lse[(int64_t)bh * prm.n_q + q] = (m + __log2f(l_tot)) * kLn2;
   } else {
-    const int64_t slot = ((int64_t)bh * prm.n_splits + split) * prm.n_resp + q;
+    const int64_t slot = ((int64_t)bh * prm.n_splits + split) * prm.n_q + q;
     float* po = prm.part_o + slot * D;
 #pragma unroll
     for (int db = 0; db < C::kDB; ++db)
@@ -335,7 +337,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_narrow_kernel(const Attend
   using C = NarrowCfg<D>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
-  const int nqt = (prm.n_resp + 31) / 32;
+  const int nqt = (prm.n_q + 31) / 32;
   const int id = blockIdx.x;
   const int bh = (id / (8 * nqt)) * 8 + id % 8;
   const int qt = (id / 8) % nqt;
@@ -358,7 +360,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_narrow_kernel(const Attend
   const int q = qt * 32 + r;
   u32x4 qf[C::kSteps];
   {
-    const char* qrow = prm.Q.row(b, h, min(q, prm.n_resp - 1));
+    const char* qrow = prm.Q.group_row(b, h, prm.q_per_kv, prm.n_resp, min(q, prm.n_q - 1));
 #pragma unroll
     for (int s = 0; s < C::kSteps; ++s) qf[s] = *reinterpret_cast<const u32x4*>(qrow + s * 32 + g * 16);
   }
@@ -479,9 +481,9 @@ __global__ __launch_bounds__(kAttThreads) void attend_narrow_kernel(const Attend
     wgt[w] = fast_exp2(v.x - M);
     L += wgt[w] * v.y;
   }
-  if (q >= prm.n_resp) return;
+  if (q >= prm.n_q) return;
   const float inv = 1.f / L;
-  char* orow = prm.O.row(b, h, q);
+  char* orow = prm.O.group_row(b, h, prm.q_per_kv, prm.n_resp, q);
   for (int db = wave; db < C::kDB; db += kAttWaves) {
 #pragma unroll
     for (int qd = 0; qd < 4; ++qd) {
@@ -499,7 +501,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_narrow_kernel(const Attend
       *reinterpret_cast<u32x2*>(orow + (db * 32 + 8 * qd + 4 * g) * 2) = wout;
     }
   }
-  if (prm.lse && wave == 0 && g == 0) prm.lse[(int64_t)bh * prm.n_resp + q] = (M + __log2f(L)) * kLn2;
+  if (prm.lse && wave == 0 && g == 0) prm.lse[(int64_t)bh * prm.n_q + q] = (M + __log2f(L)) * kLn2;
 }
 
 // Merge the key splits of the query rows: O = sum_s w_s O_s / sum_s w_s l_s, w_s = 2^(m_s - max m).
@@ -512,14 +514,14 @@ __global__ __launch_bounds__(256) void attend_merge_kernel(const AttendParams pr
   const int b = bh / prm.H, h = bh % prm.H;
   const int q = blockIdx.x * kRows + (int)threadIdx.x / kTPR;
   const int e = ((int)threadIdx.x % kTPR) * 4;
-  if (q >= prm.n_resp) return;
+  if (q >= prm.n_q) return;
   float M = kNegBig;
   for (int s = 0; s < prm.n_splits; ++s)
-    M = fmaxf(M, prm.part_ml[((int64_t)bh * prm.n_splits + s) * prm.n_resp + q].x);
+    M = fmaxf(M, prm.part_ml[((int64_t)bh * prm.n_splits + s) * prm.n_q + q].x);
   float L = 0.f;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int s = 0; s < prm.n_splits; ++s) {
-    const int64_t slot = ((int64_t)bh * prm.n_splits + s) * prm.n_resp + q;
+    const int64_t slot = ((int64_t)bh * prm.n_splits + s) * prm.n_q + q;
     const float2 ml = prm.part_ml[slot];
     const float w = fast_exp2(ml.x - M);
     const float4 v = *reinterpret_cast<const float4*>(prm.part_o + slot * D + e);
@@ -530,7 +532,7 @@ __global__ __launch_bounds__(256) void attend_merge_kernel(const AttendParams pr
     acc.w += w * v.w;
   }
   const float inv = 1.f / L;
-  char* orow = prm.O.row(b, h, q);
+  char* orow = prm.O.group_row(b, h, prm.q_per_kv, prm.n_resp, q);
   if (sizeof(T) == 2) {
     u32x2 w;
     w[0] = pack_bf16x2(acc.x * inv, acc.y * inv);
@@ -539,12 +541,12 @@ __global__ __launch_bounds__(256) void attend_merge_kernel(const AttendParams pr
   } else {
     *reinterpret_cast<float4*>(orow + e * 4) = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
   }
-  if (prm.lse && e == 0) prm.lse[(int64_t)bh * prm.n_resp + q] = (M + __log2f(L)) * kLn2;
+  if (prm.lse && e == 0) prm.lse[(int64_t)bh * prm.n_q + q] = (M + __log2f(L)) * kLn2;
 }
 
 int attend_splits(const maskkv_desc* d, bool full) {
   if (!full) return 1;
-  const int64_t qtiles = (d->n_resp + kQPerBlock - 1) / kQPerBlock;
+  const int64_t qtiles = ((int64_t)d->n_resp * query_heads_per_kv(d) + kQPerBlock - 1) / kQPerBlock;
   const int64_t blocks = qtiles * d->B * d->H;
   int64_t s = (512 + blocks - 1) / blocks;  // about two workgroups per compute unit (measured best)
   const int64_t by_len = ((int64_t)d->P_max + d->n_resp + 511) / 512;
@@ -557,7 +559,7 @@ int attend_splits(const maskkv_desc* d, bool full) {
 // The narrow kernel is used when the tiled kernel would launch fewer workgroups than there are compute units.
 bool attend_is_narrow(const maskkv_desc* d, bool full) {
   if (full || d->dtype != MASKKV_BF16) return false;
-  const int64_t qtiles = (d->n_resp + kQPerBlock - 1) / kQPerBlock;
+  const int64_t qtiles = ((int64_t)d->n_resp * query_heads_per_kv(d) + kQPerBlock - 1) / kQPerBlock;
   return qtiles * d->B * d->H < 256;
 }
 
@@ -575,7 +577,7 @@ int launch_attend_narrow(const AttendParams& prm, hipStream_t stream) {
     }
     raised = true;
   }
-  const int nqt = (prm.n_resp + 31) / 32;
+  const int nqt = (prm.n_q + 31) / 32;
   const int groups = (prm.BH + 7) / 8 * 8 * nqt;
   hipLaunchKernelGGL((attend_narrow_kernel<D>), dim3(groups), dim3(kAttThreads), C::kLds, stream, prm);
   return check_launch("attend (narrow)");
@@ -583,12 +585,12 @@ int launch_attend_narrow(const AttendParams& prm, hipStream_t stream) {
 
 template <typename T, int D>
 int launch_attend_t(const AttendParams& prm, int B, hipStream_t stream) {
-  const dim3 grid((prm.n_resp + kQPerBlock - 1) / kQPerBlock, prm.n_splits, B * prm.H);
+  const dim3 grid((prm.n_q + kQPerBlock - 1) / kQPerBlock, prm.n_splits, B * prm.H);
   hipLaunchKernelGGL((attend_kernel<T, D>), grid, dim3(kAttThreads), 0, stream, prm);
   if (int e = check_launch("attend")) return e;
   if (prm.n_splits > 1) {
     constexpr int kRows = 256 / (D / 4);
-    hipLaunchKernelGGL((attend_merge_kernel<T, D>), dim3((prm.n_resp + kRows - 1) / kRows, B * prm.H), dim3(256), 0,
+    hipLaunchKernelGGL((attend_merge_kernel<T, D>), dim3((prm.n_q + kRows - 1) / kRows, B * prm.H), dim3(256), 0,
                        stream, prm);
     return check_launch("attend merge");
   }
@@ -600,7 +602,7 @@ int launch_attend_t(const AttendParams& prm, int B, hipStream_t stream) {
 size_t attend_workspace_bytes(const maskkv_desc* d, bool full) {
   const int s = attend_splits(d, full);
   if (s == 1) return 0;
-  const size_t rows = (size_t)d->B * d->H * s * d->n_resp;
+  const size_t rows = (size_t)d->B * d->H * s * d->n_resp * query_heads_per_kv(d);
   return (rows * d->d * sizeof(float) + 255) / 256 * 256 + rows * sizeof(float2);
 }
 
@@ -620,6 +622,8 @@ int launch_attend(const maskkv_desc* d, const Lens& lens, bool full, const View&
   prm.H = d->H;
   prm.BH = d->B * d->H;
   prm.n_resp = d->n_resp;
+  prm.q_per_kv = query_heads_per_kv(d);
+  prm.n_q = d->n_resp * prm.q_per_kv;
   prm.full = full ? 1 : 0;
   prm.n_splits = attend_splits(d, full);
   prm.c = scale * kLog2e;
@@ -627,7 +631,7 @@ int launch_attend(const maskkv_desc* d, const Lens& lens, bool full, const View&
   prm.part_o = nullptr;
   prm.part_ml = nullptr;
   if (prm.n_splits > 1) {
-    const size_t rows = (size_t)d->B * d->H * prm.n_splits * d->n_resp;
+    const size_t rows = (size_t)d->B * d->H * prm.n_splits * prm.n_q;
     prm.part_o = reinterpret_cast<float*>(workspace);
     prm.part_ml = reinterpret_cast<float2*>(reinterpret_cast<char*>(workspace) +
                                             (rows * d->d * sizeof(float) + 255) / 256 * 256);

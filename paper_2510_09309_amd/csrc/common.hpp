@@ -32,7 +32,16 @@ struct View {
   __device__ __forceinline__ char* row(int b, int h, int64_t t) const {
     return ptr + boff[b] + (int64_t)h * stride_h + t * stride_t;
   }
+  // Query row r of key/value head h when g query heads of n_per rows each share that head:
+  // rows [gi*n_per, (gi+1)*n_per) are query head h*g + gi.
+  __device__ __forceinline__ char* group_row(int b, int h, int g, int n_per, int r) const {
+    const int gi = r / n_per;
+    return row(b, h * g + gi, r - gi * n_per);
+  }
 };
+
+// Query heads that share one key/value head (1 for plain multi-head attention).
+__host__ __device__ inline int query_heads_per_kv(const maskkv_desc* d) { return d->q_per_kv > 1 ? d->q_per_kv : 1; }
 
 struct Lens {
   int32_t P[MASKKV_MAX_BATCH];  // prompt length per sequence

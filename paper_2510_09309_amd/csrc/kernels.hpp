@@ -33,5 +33,7 @@ int launch_attend(const maskkv_desc* d, const Lens& lens, bool full, const View&
 size_t layer_importance_workspace_bytes();
 int launch_layer_importance(const void* h_in, const void* h_out, int64_t n, int hidden, int dtype, int64_t row_bytes,
                             float* importance, void* workspace, hipStream_t stream);
+int launch_value_shift(const void* v_now, const void* v_prev, int64_t n, int width, int dtype, int64_t row_bytes,
+                       float delta, float* cos, int32_t* refresh, int32_t* count, hipStream_t stream);
 
 }  // namespace maskkv

@@ -68,7 +68,9 @@ struct ScoreParams {
   Lens lens;
   TileMap map;        // of the pass being launched
   TileMap map1;       // of pass 1 (the merge kernel needs it to find the partial statistics)
-  int B, H, n_resp, n_query;
+  int B, H, n_resp;
+  int n_query;        // voting rows per key/value head: q_per_kv query heads of n_qh mask queries each
+  int n_qh, q_per_kv;
   int parts_p, parts_r;  // partial-statistics slots per (b, h): prompt region, response region
   float c;            // scale * log2(e)
   float2* stats;      // [B*H][parts_p + parts_r][n_query] (reference, sum) in the base-2 domain
@@ -158,13 +160,13 @@ __global__ __launch_bounds__((ScoreCfg<T, D, PASS>::kThreads), (ScoreCfg<T, D, P
         // Query fragments stay in registers for as long as the walk stays in this head.  Rows past
         // n_query re-read the last query: their statistics are never stored (pass 1) and their
         // probabilities are forced to zero through nb = -inf (pass 2).
-        const char* qbase = prm.Q.row(b, h, 0);
 #pragma unroll
         for (int blk = 0; blk < C::kNQ; ++blk) {
           const int q = min(q0 + blk * 32 + r, prm.n_query - 1);
+          const char* qrow = prm.Q.group_row(b, h, prm.q_per_kv, prm.n_qh, q);
 #pragma unroll
           for (int ks = 0; ks < C::kSteps; ++ks)
-            qf[blk][ks] = *reinterpret_cast<const u32x4*>(qbase + (int64_t)q * prm.Q.stride_t + ks * 32 + g * 16);
+            qf[blk][ks] = *reinterpret_cast<const u32x4*>(qrow + ks * 32 + g * 16);
         }
         if (PASS == 2) {
           __syncthreads();
@@ -463,9 +465,10 @@ size_t score_workspace_bytes(const maskkv_desc* d, const Lens& lens) {
   int pp, pr;
   stat_slots(d, lens, make_map(d, lens, true), &pp, &pr);
   const int64_t bh = (int64_t)d->B * d->H;
-  size_t stats = (size_t)(bh * (pp + pr) * d->n_query) * sizeof(float2);
+  const int64_t nq = (int64_t)d->n_query * query_heads_per_kv(d);
+  size_t stats = (size_t)(bh * (pp + pr) * nq) * sizeof(float2);
   stats = (stats + 255) / 256 * 256;
-  const size_t lse = (size_t)(bh * d->n_query) * sizeof(float);
+  const size_t lse = (size_t)(bh * nq) * sizeof(float);
   return stats + (lse + 255) / 256 * 256;
 }
 
@@ -481,11 +484,13 @@ int launch_score(const maskkv_desc* d, const View& Q, const View& K, const Lens&
   prm.B = d->B;
   prm.H = d->H;
   prm.n_resp = d->n_resp;
-  prm.n_query = d->n_query;
+  prm.q_per_kv = query_heads_per_kv(d);
+  prm.n_qh = d->n_query;
+  prm.n_query = d->n_query * prm.q_per_kv;
   stat_slots(d, lens, prm.map1, &prm.parts_p, &prm.parts_r);
   prm.c = scale * kLog2e;
   const int64_t bh = (int64_t)d->B * d->H;
-  size_t stats = (size_t)(bh * (prm.parts_p + prm.parts_r) * d->n_query) * sizeof(float2);
+  size_t stats = (size_t)(bh * (prm.parts_p + prm.parts_r) * prm.n_query) * sizeof(float2);
   stats = (stats + 255) / 256 * 256;
   prm.stats = reinterpret_cast<float2*>(workspace);
   prm.lse2 = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + stats);

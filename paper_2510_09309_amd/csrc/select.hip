@@ -522,7 +522,7 @@ int launch_select(const maskkv_desc* d, const Lens& lens, const float* scores, i
 
 int launch_head_budgets(const maskkv_desc* d, const float* prompt_mass, int32_t k_l, float alpha, int32_t* budgets,
                         hipStream_t stream) {
-  BudgetParams prm{d->H, d->n_query, prompt_mass, k_l, alpha, budgets};
+  BudgetParams prm{d->H, d->n_query * query_heads_per_kv(d), prompt_mass, k_l, alpha, budgets};
   hipLaunchKernelGGL(head_budgets_kernel, dim3(d->B), dim3(256), 0, stream, prm);
   return check_launch("head_budgets");
 }

@@ -118,6 +118,32 @@ def make_hidden_states(seed: int, n: int, hidden: int, dtype: str, drift: float)
     return h_in, h_out
 
 
+def make_value_steps(seed: int, n: int, width: int, dtype: str, drift_lo: float, drift_hi: float):
+    """Stand-ins for one layer's value features of the n response tokens at two consecutive denoising steps,
+    [n, width] each: the earlier step is Gaussian, the later one adds Gaussian noise whose size is drawn per
+    token uniformly in [drift_lo, drift_hi], so the per-token cosine similarities spread over a range (about
+    1/sqrt(1 + drift^2)).  Returns (V_now, V_prev) as float32 arrays holding the rounded values."""
+    rng = np.random.default_rng(seed)
+    v_prev = rng.standard_normal((n, width)).astype(np.float32)
+    drift = rng.uniform(drift_lo, drift_hi, size=(n, 1)).astype(np.float32)
+    v_now = v_prev + drift * rng.standard_normal((n, width)).astype(np.float32)
+    if dtype == "bf16":
+        return round_to_bf16(v_now), round_to_bf16(v_prev)
+    return v_now, v_prev
+
+
+def make_grouped_queries(seed: int, base: LayerInputs, q_per_kv: int, sigma: float = 1.0,
+                         query_shift: float = 1.0) -> np.ndarray:
+    """Queries for a grouped-query layer: [H * q_per_kv, n_m, d], query heads h*g .. h*g+g-1 reading KV head h of
+    `base`.  Same recipe as make_layer's queries; the heads of a group share their KV head's planted direction."""
+    rng = np.random.default_rng(seed)
+    s = np.float32(sigma / np.sqrt(base.d))
+    Q = rng.standard_normal((base.H * q_per_kv, base.n_m, base.d), dtype=np.float32) * s
+    for hq in range(base.H * q_per_kv):
+        Q[hq] += np.float32(query_shift) * base.u[hq // q_per_kv]
+    return _store(Q, base.dtype)
+
+
 def budgets_two_level(H: int, avg: int, seed: int, ratio: int = 2) -> np.ndarray:
     """Per-head integer budgets summing to H*avg: half the heads (seeded choice) get ``ratio`` x the others.
 

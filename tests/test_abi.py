@@ -51,6 +51,10 @@ def test_workspace_sizes(mk):
     assert mk.maskkv_select_workspace_bytes(d) == 32 * 32768 * 8  # (key, position) candidates, 4096 per chunk
     assert mk.maskkv_attend_workspace_bytes(d, False) == 0
     assert mk.maskkv_attend_workspace_bytes(d, True) > 0
+    grouped = mk.Desc(B=1, H=4, d=128, dtype=mk.MASKKV_BF16, n_resp=256, P_max=32768, q_per_kv=7)
+    single = mk.Desc(B=1, H=4, d=128, dtype=mk.MASKKV_BF16, n_resp=256, P_max=32768)
+    assert mk.maskkv_score_workspace_bytes(grouped) > 6 * mk.maskkv_score_workspace_bytes(single)   # 7x the voting rows
+    assert mk.maskkv_select_workspace_bytes(grouped) == mk.maskkv_select_workspace_bytes(single)   # per KV head
     long = mk.Desc(B=2, H=4, d=128, dtype=mk.MASKKV_BF16, n_resp=8, P_max=100000)
     assert mk.maskkv_select_workspace_bytes(long) == 2 * 4 * 25 * 4096 * 8
 
@@ -58,6 +62,7 @@ def test_workspace_sizes(mk):
 @pytest.mark.parametrize("kw,status", [
     (dict(d=96), 2), (dict(dtype=7), 3), (dict(B=0), 2), (dict(B=65), 2), (dict(n_resp=0), 1),
     (dict(P_max=-1), 1), (dict(prompt_len=[5000]), 1), (dict(H=0), 2),
+    (dict(q_per_kv=-1), 1), (dict(q_per_kv=65), 1), (dict(q_per_kv=64, n_resp=1 << 15), 2),
 ])
 def test_bad_descriptions_are_rejected(mk, kw, status):
     base = dict(B=1, H=4, d=128, dtype=mk.MASKKV_BF16, n_resp=16, P_max=1024)
@@ -102,6 +107,15 @@ def test_bad_call_arguments_are_rejected_before_launch(mk):
     assert lib.maskkv_head_budgets(ct.byref(desc), f, ct.c_int32(10), ct.c_float(1.5), f, None) == 1
     assert lib.maskkv_head_budgets(ct.byref(desc), f, ct.c_int32(-1), ct.c_float(0.1), f, None) == 1
     assert b"alpha" in lib.maskkv_last_error()
+    shift = lambda a, b, n, width, dtype, stride, delta: lib.maskkv_value_shift(
+        a, b, ct.c_int64(n), ct.c_int32(width), ct.c_int32(dtype), ct.c_int64(stride), ct.c_float(delta), f, f, f, None)
+    assert shift(f, None, 10, 64, 0, 64, 0.9) == 1             # NULL input
+    assert shift(f, f, 0, 64, 0, 64, 0.9) == 1                 # no tokens
+    assert shift(f, f, 10, 60, 0, 64, 0.9) == 1                # width not a multiple of 8
+    assert shift(f, f, 10, 64, 0, 32, 0.9) == 1                # row stride below the width
+    assert shift(f, f, 10, 64, 1, 68, 0.9) == 1                # bf16 rows of 136 bytes: not 16-byte multiples
+    assert shift(f, f, 10, 64, 5, 64, 0.9) == 3                # unknown dtype
+    assert shift(f, f, 10, 64, 0, 64, float("nan")) == 1
 
 
 def test_layer_budgets_host_arithmetic_matches_the_oracle(mk):
