@@ -302,6 +302,37 @@ def test_attend_wide_launch_takes_the_tiled_kernel():
             assert np.abs(lse_h[b, h] - rl).max() <= 1e-3
 
 
+@pytest.mark.parametrize("d,n_m,sigma", [(128, 512, 1.0), (64, 250, 1.0), (128, 256, 9.5)])
+def test_attend_many_heads_long_response_span(d, n_m, sigma):
+    """128 heads with response spans of several query tiles: ragged budgets from an empty cache to the whole
+    prompt, a key axis that ends inside a 32-key block, peaky logits, compressed and un-evicted calls."""
+    B, H = 2, 64
+    layers = [synth.make_layer(1300 + b, H=H, d=d, P=333 + 120 * b, n_m=n_m, dtype="bf16", n_planted=6, amplitude=2.5,
+                               sigma=sigma) for b in range(B)]
+    batch = hp.Batch(layers)
+    assert B * H * ((n_m + 255) // 256) >= 128
+    budgets = synth.budgets_log_uniform(B * H, 8, 300, seed=78)
+    budgets[0], budgets[1], budgets[H] = 0, 10 ** 6, 453
+    scores, _ = hp.gpu_score(batch)
+    idx, cu, cap = hp.gpu_select(batch, scores, budgets, 7)
+    keeps, _ = hp.split_idx(idx, cu)
+    Kc, Vc = hp.gpu_compact(batch, idx, cu, cap)
+    O, lse = hp.gpu_attend(batch, Kc, Vc, cu, cap)
+    O2, lse2 = hp.gpu_attend_full(batch)
+    O_h, lse_h = O.float().cpu().numpy(), lse.cpu().numpy().reshape(B, H, n_m)
+    O2_h, lse2_h = O2.float().cpu().numpy(), lse2.cpu().numpy().reshape(B, H, n_m)
+    assert np.isfinite(O_h).all() and np.isfinite(O2_h).all()
+    for b, L in enumerate(layers):
+        for h in (0, 1, 17, 63):
+            keep = keeps[b * H + h]
+            ref, rl = orc.attend(L.Q[h], L.K[h, keep], L.V[h, keep], L.K[h, L.P:], L.V[h, L.P:], return_lse=True)
+            assert np.abs(O_h[b, h] - ref).max() <= hp.ATTEND_ATOL_BF16, (b, h)
+            assert np.abs(lse_h[b, h] - rl).max() <= 1e-3
+            ref2, rl2 = orc.attend_full(L.Q[h], L.K[h], L.V[h], return_lse=True)
+            assert np.abs(O2_h[b, h] - ref2).max() <= hp.ATTEND_ATOL_BF16, (b, h)
+            assert np.abs(lse2_h[b, h] - rl2).max() <= 1e-3
+
+
 def test_repeated_calls_are_deterministic():
     L = synth.make_layer(83, H=4, d=128, P=5000, n_m=256, dtype="bf16", n_planted=50, amplitude=2.5)
     batch = hp.Batch([L])
