@@ -164,6 +164,76 @@ def layer_stack(torch, mk, cfg, desc, n_layers, have, stride):
             "kept_rows_per_layer_min_max": [min(kept), max(kept)], "capacity_per_layer": cap}
 
 
+def batched_ragged(torch, mk, synth, steps=64):
+    """The batched ragged configuration: 8 sequences, prompts drawn in 4k..16k, 512 mask queries, per-head budgets
+    log-uniform in 64..1024.  Compression once (score, select, compact over the ragged batch), then `steps`
+    denoising steps that each attend with fresh response Q/K/V over the fixed evicted cache.  This is the shape at
+    which the gather moves enough bytes, and the attention enough flops, for a rate to mean something."""
+    B, H, d, n_m = 8, 32, 128, 512
+    P = [int(x) for x in synth.c5_prompt_lengths()]
+    P_max = max(P)
+    desc = mk.Desc(B=B, H=H, d=d, dtype=mk.MASKKV_BF16, n_resp=n_m, P_max=P_max, prompt_len=P)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3000)
+    sc = 1.0 / d ** 0.5
+    dev = dict(device="cuda")
+
+    def gauss(shape):
+        return (torch.randn(shape, generator=g, dtype=torch.float32, **dev) * sc).to(torch.bfloat16)
+    K, V, Q = gauss((B, H, P_max + n_m, d)), gauss((B, H, P_max + n_m, d)), gauss((B, H, n_m, d))
+    u = torch.randn((B, H, d), generator=g, dtype=torch.float32, **dev)
+    u = (u / u.norm(dim=2, keepdim=True)).to(torch.bfloat16)
+    Q += u[:, :, None, :]                      # same recipe as device_layer: a direction per head shared by the
+    for b in range(B):                         # mask queries and 2 % planted prompt keys (amplitude 2.5)
+        for h in range(H):
+            pos = torch.randperm(P[b], generator=g, device="cuda")[:round(0.02 * P[b])]
+            K[b, h, pos] += 2.5 * u[b, h]
+    fresh = [(gauss((B, H, n_m, d)), gauss((B, H, n_m, d)), gauss((B, H, n_m, d))) for _ in range(4)]
+    bud_h = synth.budgets_log_uniform(B * H, 64, 1024, 3000).astype(np.int32)
+    budgets = torch.from_numpy(bud_h).cuda()
+    cap = int(bud_h.sum())
+    stride = (P_max + 63) // 64 * 64
+    scores = torch.empty((B * H, stride), dtype=torch.float32, **dev)
+    mass = torch.empty(B * H, dtype=torch.float32, **dev)
+    idx = torch.empty(cap, dtype=torch.int32, **dev)
+    cu = torch.empty(B * H + 1, dtype=torch.int32, **dev)
+    Kc = torch.empty((cap, d), dtype=torch.bfloat16, **dev)
+    Vc = torch.empty_like(Kc)
+    O = torch.empty((B, H, n_m, d), dtype=torch.bfloat16, **dev)
+    ws = lambda n: torch.empty(max(n, 256), dtype=torch.uint8, **dev)
+    w_sc, w_sel = ws(mk.maskkv_score_workspace_bytes(desc)), ws(mk.maskkv_select_workspace_bytes(desc))
+    w_att = ws(mk.maskkv_attend_workspace_bytes(desc, False))
+
+    def timed(fn, reps):
+        fn(0)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for i in range(reps):
+            fn(i)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+    t_score = timed(lambda i: mk.maskkv_score(desc, Q, K, 0.0, scores, stride, mass, w_sc), 4)
+    t_select = timed(lambda i: mk.maskkv_select(desc, scores, stride, 7, mk.POOL_MEAN, budgets, idx, cu, cap, w_sel), 8)
+    t_compact = timed(lambda i: mk.maskkv_compact(desc, K, V, idx, cu, cap, Kc, Vc), 8)
+    t_attend = timed(lambda i: mk.maskkv_attend(desc, fresh[i % 4][0], Kc, Vc, cu, cap, fresh[i % 4][1], fresh[i % 4][2],
+                                                0.0, O, None, w_att), steps)
+    flop_qk = 2.0 * n_m * d * H * sum(p + n_m for p in P)
+    flop_att = 4.0 * n_m * d * (cap + B * H * n_m)
+    return {"workload": f"C5: {B} sequences, prompts {min(P)}..{max(P)} (sum {sum(P)}), {H} heads x {d}, bf16, {n_m} mask "
+                        f"queries, budgets 64..1024 log-uniform ({cap} kept rows); {steps} denoising steps",
+            "ms": {"score": t_score, "select": t_select, "compact": t_compact, "attend_per_step": t_attend},
+            "prompt_tokens_scored_evicted_per_s": sum(P) / ((t_score + t_select + t_compact) * 1e-3),
+            "score_tflops_algorithmic": flop_qk / (t_score * 1e-3) / 1e12,
+            "select_gbs": (4.0 * H * sum(P) + 4.0 * cap) / (t_select * 1e-3) / 1e9,
+            "gather_gbs": 2.0 * 2 * cap * d * 2 / (t_compact * 1e-3) / 1e9,
+            "gather_frac_of_hbm_peak": 2.0 * 2 * cap * d * 2 / (t_compact * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "attend_tflops": flop_att / (t_attend * 1e-3) / 1e12,
+            "attend_frac_of_mfma_peak": flop_att / (t_attend * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "compress_once_plus_steps_ms": t_score + t_select + t_compact + steps * t_attend}
+
+
 def layer_importance_rate(torch, mk, n_tokens, hidden=4096):
     """Layer-importance reduction over [n_tokens, hidden] bf16 hidden states (LLaDA-8B's width): HBM-bound."""
     sets = []
@@ -234,6 +304,9 @@ def main():
                     help="after the timed region, also run a whole stack of this many resident layers "
                          "(score -> on-device head budgets -> select -> compact -> attend per layer), eagerly and "
                          "as one HIP graph; 0 skips it")
+    ap.add_argument("--no-batched", action="store_true",
+                    help="skip the batched ragged configuration (8 sequences, 64 denoising steps) that is run after "
+                         "the timed region")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="before the warm-up, copy 256 MiB device-to-device three times: a kernel of known traffic "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
@@ -377,6 +450,9 @@ def main():
     if args.stack_layers > 0:
         out["stack"] = layer_stack(torch, mk, cfg, desc, args.stack_layers, layers, stride)
         out["layer_importance"] = layer_importance_rate(torch, mk, N)
+    if not args.no_batched:
+        del layers, resp
+        out["batched"] = batched_ragged(torch, mk, synth)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_oracle_baseline(cfg)
     print(json.dumps(out))
