@@ -129,8 +129,16 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const AttendParams 
   __shared__ __attribute__((aligned(16))) char kt[C::kTK * C::kRowP];
   __shared__ __attribute__((aligned(16))) char vt[D * C::kSV * sizeof(T)];
 
-  const int bh = blockIdx.z;
-  const int split = blockIdx.y;
+  // Workgroup numbers that are congruent modulo 8 run on the same XCD and share its L2.  The query tiles of
+  // one (head, key split) read the same K/V rows, so they are given consecutive slots of one XCD: the rows
+  // then come from HBM once instead of once per query tile.
+  const int qtiles = (prm.n_q + kQPerBlock - 1) / kQPerBlock;
+  const int slot = blockIdx.x / 8;
+  const int unit = (slot / qtiles) * 8 + blockIdx.x % 8;  // (head, split) pair
+  const int qtile = slot % qtiles;
+  if (unit >= prm.BH * prm.n_splits) return;
+  const int bh = unit / prm.n_splits;
+  const int split = unit % prm.n_splits;
   const int b = bh / prm.H;
   const int h = bh % prm.H;
   const int lane = threadIdx.x & 63;
@@ -157,7 +165,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const AttendParams 
   const int j1 = min(Lk, j0 + Ls);
   const int ntiles = j1 > j0 ? (j1 - j0 + C::kTK - 1) / C::kTK : 0;
 
-  const int q = blockIdx.x * kQPerBlock + wave * 32 + r;
+  const int q = qtile * kQPerBlock + wave * 32 + r;
   u32x4 qf[C::kSteps];
 #pragma unroll
   for (int s = 0; s < C::kSteps; ++s) {
@@ -585,8 +593,13 @@ int launch_attend_narrow(const AttendParams& prm, hipStream_t stream) {
 
 template <typename T, int D>
 int launch_attend_t(const AttendParams& prm, int B, hipStream_t stream) {
-  const dim3 grid((prm.n_q + kQPerBlock - 1) / kQPerBlock, prm.n_splits, B * prm.H);
-  hipLaunchKernelGGL((attend_kernel<T, D>), grid, dim3(kAttThreads), 0, stream, prm);
+  const int64_t qtiles = (prm.n_q + kQPerBlock - 1) / kQPerBlock;
+  const int64_t units = ((int64_t)B * prm.H * prm.n_splits + 7) / 8 * 8;  // (head, split) pairs, whole rounds of XCDs
+  if (units * qtiles > 0x7FFFFFFF) {
+    set_error("attend: %lld workgroups exceed the launch limit", (long long)(units * qtiles));
+    return MASKKV_ESHAPE;
+  }
+  hipLaunchKernelGGL((attend_kernel<T, D>), dim3((unsigned)(units * qtiles)), dim3(kAttThreads), 0, stream, prm);
   if (int e = check_launch("attend")) return e;
   if (prm.n_splits > 1) {
     constexpr int kRows = 256 / (D / 4);
