@@ -18,6 +18,7 @@ namespace {
 constexpr int kAttThreads = 256;
 constexpr int kAttWaves = 4;
 constexpr int kQPerBlock = kAttWaves * 32;
+constexpr float kLazyBump = 8.f;  // log2 of the largest probability tolerated before the running reference is raised
 
 template <typename T, int D>
 struct AttCfg {
@@ -218,23 +219,31 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const AttendParams 
 #pragma unroll
       for (int i = 0; i < 16; ++i) bm = fmaxf(bm, s[kb][i]);
     bm = fmaxf(bm, xor32(bm));
-    const float m_new = fmaxf(m, bm * c);
-    const float alpha = fast_exp2(m - m_new);
+    // The reference m is only raised when a tile exceeds it by more than 2^kLazyBump: probabilities then stay
+    // below 2^kLazyBump (harmless in fp32 sums and as bf16 operands, whose exponent range is fp32's), and the
+    // accumulators are rescaled on few tiles only.
+    const float cand = bm * c;
+    const bool bump = cand > m + kLazyBump;
+    if (__any(bump)) {
+      const float m_new = bump ? cand : m;
+      const float alpha = fast_exp2(m - m_new);
+      m = m_new;
+      l *= alpha;
+#pragma unroll
+      for (int db = 0; db < C::kDB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+    }
     float psum = 0.f;
 #pragma unroll
     for (int kb = 0; kb < C::kNKB; ++kb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const float p = fast_exp2(fmaf(s[kb][i], c, -m_new));
+        const float p = fast_exp2(fmaf(s[kb][i], c, -m));
         s[kb][i] = p;
         psum += p;
       }
-    l = l * alpha + psum;
-    m = m_new;
-#pragma unroll
-    for (int db = 0; db < C::kDB; ++db)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+    l += psum;
 
     // O^T += V^T P^T
     if (sizeof(T) == 2) {
