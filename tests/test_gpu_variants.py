@@ -102,6 +102,57 @@ def test_grouped_queries_wide_launch():
     run_grouped(seed=4300, H=8, g=4, d=128, P=520, n_m=1000, dtype="bf16", budgets=[100] * 4 + [37] * 4)
 
 
+def test_grouped_queries_ragged_batch_token_major_layout():
+    """Two sequences of different prompt length, g = 3, tensors stored [B, T, heads, d]: the query-head stride is
+    then not a multiple of the token stride, and query tiles straddle query heads (n_resp = 40)."""
+    m = hp.mk()
+    B, H, g, d, n_m, dtype = 2, 2, 3, 128, 40, "bf16"
+    Ps = [700, 413]
+    P_max, N_max = max(Ps), max(Ps) + n_m
+    Ls = [synth.make_layer(4500 + b, H, d, Ps[b], n_m, dtype, n_planted=9, amplitude=2.5) for b in range(B)]
+    Qg = [synth.make_grouped_queries(4510 + b, Ls[b], g) for b in range(B)]
+    Kh = np.zeros((B, H, N_max, d), dtype=np.float32)
+    Vh = np.zeros_like(Kh)
+    for b, L in enumerate(Ls):
+        Kh[b, :, :L.N], Vh[b, :, :L.N] = L.K, L.V
+    token_major = lambda x: hp.upload(x, dtype).permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    K, V, Q = token_major(Kh), token_major(Vh), token_major(np.stack(Qg))
+    assert Q.stride(1) == d and Q.stride(2) == H * g * d
+    desc = m.Desc(B=B, H=H, d=d, dtype=m.MASKKV_BF16, n_resp=n_m, P_max=P_max, prompt_len=Ps, q_per_kv=g)
+    stride = (P_max + 63) // 64 * 64
+    scores = torch.full((B * H, stride), float("nan"), dtype=torch.float32, device="cuda")
+    m.maskkv_score(desc, Q, K, 0.0, scores, stride, None, hp.workspace(m.maskkv_score_workspace_bytes(desc)))
+    budgets = np.array([50, 0, 413, 77], dtype=np.int32)
+    cap = int(budgets.sum())
+    idx = torch.full((cap,), -1, dtype=torch.int32, device="cuda")
+    cu = torch.full((B * H + 1,), -1, dtype=torch.int32, device="cuda")
+    m.maskkv_select(desc, scores, stride, 7, 0, torch.from_numpy(budgets).cuda(), idx, cu, cap,
+                    hp.workspace(m.maskkv_select_workspace_bytes(desc)))
+    Kc = torch.zeros((cap, d), dtype=torch.bfloat16, device="cuda")
+    Vc = torch.zeros_like(Kc)
+    m.maskkv_compact(desc, K, V, idx, cu, cap, Kc, Vc)
+    O = torch.full((B, n_m, H * g, d), float("nan"), dtype=torch.bfloat16, device="cuda").permute(0, 2, 1, 3)
+    lse = torch.full((B * H * g * n_m,), float("nan"), dtype=torch.float32, device="cuda")
+    Kr, Vr = m.tensor_view(K, seq_start=Ps), m.tensor_view(V, seq_start=Ps)
+    m.maskkv_attend(desc, Q, Kc, Vc, cu, cap, Kr, Vr, 0.0, O, lse, hp.workspace(m.maskkv_attend_workspace_bytes(desc, False)))
+    torch.cuda.synchronize()
+    sc = scores.cpu().numpy()
+    keeps, _ = hp.split_idx(idx, cu)
+    O_h, lse_h = O.float().cpu().numpy(), lse.cpu().numpy().reshape(B, H * g, n_m)
+    for b, L in enumerate(Ls):
+        for h in range(H):
+            I, _ = orc.score_grouped(Qg[b][h * g:(h + 1) * g], L.K[h], L.P)
+            assert (np.abs(sc[b * H + h, :L.P] - I) / I).max() <= hp.SCORE_RTOL
+            keep = keeps[b * H + h]
+            hp.check_keep_against_oracle(orc.pool(I, 7), int(budgets[b * H + h]), keep, f"b={b} h={h}")
+            want = orc.attend_grouped(Qg[b][h * g:(h + 1) * g], L.K[h, keep], L.V[h, keep], L.K[h, L.P:], L.V[h, L.P:])
+            assert np.abs(O_h[b, h * g:(h + 1) * g] - want).max() <= hp.ATTEND_ATOL_BF16
+            for gi in range(g):
+                _, rl = orc.attend(Qg[b][h * g + gi], L.K[h, keep], L.V[h, keep], L.K[h, L.P:], L.V[h, L.P:],
+                                   return_lse=True)
+                assert np.abs(lse_h[b, h * g + gi] - rl).max() <= 1e-3
+
+
 def test_group_of_one_is_multi_head_attention():
     """q_per_kv = 1 and q_per_kv = 0 give the same bits as each other."""
     m = hp.mk()
