@@ -234,6 +234,33 @@ def batched_ragged(torch, mk, synth, steps=64):
             "compress_once_plus_steps_ms": t_score + t_select + t_compact + steps * t_attend}
 
 
+def measured_peaks(torch, mk):
+    """What this machine sustains on the three resources that bound the kernels, from the library's probe kernels:
+    bf16 MFMA issue from registers, v_exp_f32, and a streaming copy (bytes read + written)."""
+    out = torch.empty(2048 * 256, dtype=torch.float32, device="cuda")
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
+    dst = torch.empty_like(src)
+
+    def rate(fn, reps):
+        work = fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return work * reps / (a.elapsed_time(b) * 1e-3)
+    mfma = rate(lambda: mk.maskkv_probe(0, 20000, None, out, 512), 3)     # two waves per SIMD
+    exps = rate(lambda: mk.maskkv_probe(1, 20000, None, out, 2048), 3)    # eight waves per SIMD
+    copy = rate(lambda: mk.maskkv_probe(2, 0, src, dst, 2048), 5)
+    read = rate(lambda: mk.maskkv_probe(3, 0, src, out, 2048), 5)
+    return {"mfma_bf16_tflops": mfma / 1e12, "v_exp_f32_per_s": exps, "stream_copy_gbs": copy / 1e9,
+            "stream_read_gbs": read / 1e9,
+            "how": "maskkv_probe: register-only v_mfma_f32_32x32x16_bf16 loop on 512 workgroups, v_exp_f32 loop on "
+                   "2048 workgroups, 1 GiB copy (read + written bytes), 1 GiB read"}
+
+
 def layer_importance_rate(torch, mk, n_tokens, hidden=4096):
     """Layer-importance reduction over [n_tokens, hidden] bf16 hidden states (LLaDA-8B's width): HBM-bound."""
     sets = []
@@ -450,6 +477,15 @@ def main():
     if args.stack_layers > 0:
         out["stack"] = layer_stack(torch, mk, cfg, desc, args.stack_layers, layers, stride)
         out["layer_importance"] = layer_importance_rate(torch, mk, N)
+    peaks = measured_peaks(torch, mk)
+    n_exp = float(n_m) * N * H                       # exponentials of one pass
+    peaks["score_pass1_vs_measured"] = {
+        "frac_of_measured_mfma": out["roofline"]["achieved"] / peaks["mfma_bf16_tflops"],
+        "mfma_time_us": flop_qk_all / (peaks["mfma_bf16_tflops"] * 1e12) * 1e6,
+        "exp_time_us": n_exp / peaks["v_exp_f32_per_s"] * 1e6,
+        "k_stream_time_us": bytes_k / (peaks["stream_read_gbs"] * 1e9) * 1e6,
+        "measured_us": pass1_ms * 1e3}
+    out["measured_peaks"] = peaks
     if not args.no_batched:
         del layers, resp
         out["batched"] = batched_ragged(torch, mk, synth)

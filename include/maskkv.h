@@ -251,6 +251,21 @@ int maskkv_layer_budgets(const float* importance, int32_t n_layers, int64_t k_p,
 int maskkv_value_shift(const void* V_now, const void* V_prev, int64_t n_tokens, int32_t width, int32_t dtype,
                        int64_t row_stride, float delta, float* cos, int32_t* refresh, int32_t* count, void* stream);
 
+/*
+ * Measurement probe (not part of the method; for roofline harnesses): enqueues one kernel that exercises a
+ * single resource, so that the caller can time it and quote kernel rates against what this chip sustains.
+ *   which = 0  bf16 matrix pipe: every wave of `groups` 256-thread workgroups issues 4*iters
+ *              v_mfma_f32_32x32x16_bf16 from registers;      *work = floating-point operations
+ *   which = 1  v_exp_f32: every lane issues 8*iters exponentials;               *work = exponentials
+ *   which = 2  streaming copy of `bytes` from src to dst (grid-stride, 16-byte pieces); *work = bytes read + written
+ *   which = 3  streaming read of `bytes` from src (folded into one word per thread);     *work = bytes read
+ * dst: DEVICE of dst_bytes bytes; for which != 2 it receives groups*256 32-bit words, for which = 2 it is the copy
+ * target.  src: DEVICE, 16-byte aligned, `bytes` a multiple of 16 (which >= 2; ignored otherwise).  work: HOST
+ * double, may be NULL.  groups: 256-thread workgroups launched, 1..2^20.  MASKKV_EINVAL on any violation.
+ */
+int maskkv_probe(int which, int32_t iters, const void* src, void* dst, int64_t bytes, int64_t dst_bytes,
+                 int32_t groups, void* stream, double* work);
+
 #ifdef __cplusplus
 }
 #endif

@@ -30,7 +30,7 @@ SYMBOLS = [
     "maskkv_attend_workspace_bytes", "maskkv_attend", "maskkv_attend_full",
     "maskkv_head_budgets",
     "maskkv_layer_importance_workspace_bytes", "maskkv_layer_importance", "maskkv_layer_budgets",
-    "maskkv_value_shift",
+    "maskkv_value_shift", "maskkv_probe",
 ]
 
 
@@ -260,6 +260,18 @@ def maskkv_value_shift(V_now: torch.Tensor, V_prev: torch.Tensor, delta: float, 
     _check(_lib.maskkv_value_shift(_ptr(V_now), _ptr(V_prev), ct.c_int64(V_now.shape[0]), ct.c_int32(V_now.shape[1]),
                                    ct.c_int32(_dtype_code(V_now)), ct.c_int64(V_now.stride(0)), ct.c_float(delta),
                                    _ptr(cos), _ptr(refresh), _ptr(count), _stream(stream)), "maskkv_value_shift")
+
+
+def maskkv_probe(which: int, iters: int, src: Optional[torch.Tensor], dst: torch.Tensor, groups: int,
+                 stream=None) -> float:
+    """Enqueue a measurement probe (0 matrix pipe, 1 v_exp_f32, 2 streaming copy src -> dst, 3 streaming read of
+    src); returns the work it does (flops, exponentials or bytes moved)."""
+    work = ct.c_double(0.0)
+    nbytes = src.numel() * src.element_size() if src is not None else 0
+    _check(_lib.maskkv_probe(ct.c_int(which), ct.c_int32(iters), _ptr(src) if src is not None else None, _ptr(dst),
+                             ct.c_int64(nbytes), ct.c_int64(dst.numel() * dst.element_size()), ct.c_int32(groups),
+                             _stream(stream), ct.byref(work)), "maskkv_probe")
+    return float(work.value)
 
 
 def raw_library() -> ct.CDLL:

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmaskkv.so")
-SOURCES = ["api.hip", "score.hip", "select.hip", "compact.hip", "attend.hip", "layer.hip"]
+SOURCES = ["api.hip", "score.hip", "select.hip", "compact.hip", "attend.hip", "layer.hip", "probe.hip"]
 FLAGS = [
     "-shared", "-fPIC", "-O3", "-std=c++17", "--offload-arch=gfx950",
     # packed fp32 arithmetic is kept off for every kernel in this library

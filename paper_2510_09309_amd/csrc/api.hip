@@ -353,6 +353,34 @@ int maskkv_value_shift(const void* V_now, const void* V_prev, int64_t n_tokens, 
                             reinterpret_cast<hipStream_t>(stream));
 }
 
+int maskkv_probe(int which, int32_t iters, const void* src, void* dst, int64_t bytes, int64_t dst_bytes,
+                 int32_t groups, void* stream, double* work) {
+  if (which < 0 || which > 3 || !dst || groups < 1 || groups > (1 << 20)) {
+    set_error("probe: which %d outside 0..3, dst NULL or groups %d outside 1..2^20", which, groups);
+    return MASKKV_EINVAL;
+  }
+  if (which != 2 && dst_bytes < (int64_t)groups * 256 * 4) {
+    set_error("probe: dst of %lld bytes is smaller than groups*256 words", (long long)dst_bytes);
+    return MASKKV_EINVAL;
+  }
+  if (which < 2) {
+    if (iters < 1) {
+      set_error("probe: iters %d < 1", iters);
+      return MASKKV_EINVAL;
+    }
+    // floating-point operations (which = 0: 2*32*32*16 per MFMA, 4 waves x 4 MFMAs per iteration) or exponentials
+    if (work) *work = which == 0 ? (double)groups * 4 * 4 * iters * 32768.0 : (double)groups * 256 * 8 * iters;
+  } else {
+    if (!src || bytes < 16 || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15) ||
+        (which == 2 && dst_bytes < bytes)) {
+      set_error("probe: streaming needs 16-byte aligned src and dst, a positive multiple of 16 bytes, and room in dst");
+      return MASKKV_EINVAL;
+    }
+    if (work) *work = which == 2 ? 2.0 * (double)bytes : (double)bytes;  // bytes read (+ written)
+  }
+  return launch_probe(which, iters, src, dst, bytes, groups, reinterpret_cast<hipStream_t>(stream));
+}
+
 int maskkv_layer_budgets(const float* importance, int32_t n_layers, int64_t k_p, float beta, const int32_t* boundary,
                          int32_t n_boundary, int64_t* k_l) {
   if (!importance || !k_l || n_layers < 1 || k_p < 0 || !(beta >= 0.f && beta <= 1.f) || n_boundary < 0 ||

@@ -107,6 +107,16 @@ def test_bad_call_arguments_are_rejected_before_launch(mk):
     assert lib.maskkv_head_budgets(ct.byref(desc), f, ct.c_int32(10), ct.c_float(1.5), f, None) == 1
     assert lib.maskkv_head_budgets(ct.byref(desc), f, ct.c_int32(-1), ct.c_float(0.1), f, None) == 1
     assert b"alpha" in lib.maskkv_last_error()
+    probe = lambda which, iters, src, nbytes, dst_bytes, groups: lib.maskkv_probe(
+        ct.c_int(which), ct.c_int32(iters), src, f, ct.c_int64(nbytes), ct.c_int64(dst_bytes), ct.c_int32(groups), None,
+        None)
+    assert probe(4, 10, None, 0, 1 << 20, 8) == 1              # unknown probe
+    assert probe(0, 0, None, 0, 1 << 20, 8) == 1               # no iterations
+    assert probe(0, 10, None, 0, 8 * 256 * 4 - 4, 8) == 1      # result buffer too small
+    assert probe(2, 0, None, 1024, 1024, 8) == 1               # copy without a source
+    assert probe(2, 0, f, 1000, 1024, 8) == 1                  # not a multiple of 16 bytes
+    assert probe(2, 0, f, 2048, 1024, 8) == 1                  # copy target too small
+    assert probe(3, 0, f, 2048, 1024, 8) == 1                  # read: result buffer too small
     shift = lambda a, b, n, width, dtype, stride, delta: lib.maskkv_value_shift(
         a, b, ct.c_int64(n), ct.c_int32(width), ct.c_int32(dtype), ct.c_int64(stride), ct.c_float(delta), f, f, f, None)
     assert shift(f, None, 10, 64, 0, 64, 0.9) == 1             # NULL input

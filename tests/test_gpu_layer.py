@@ -65,3 +65,30 @@ def test_importance_feeds_layer_budgets():
     want = orc.layer_budgets(np.array(imps, dtype=np.float32).astype(np.float64), k_p, np.float64(np.float32(0.4)))
     assert got == want.tolist() and sum(got) <= k_p
     assert got[0] > got[1] and got[-1] > got[2]   # the drifting boundary layers receive more
+
+
+def test_measurement_probes_run_and_the_copy_is_exact():
+    m = hp.mk()
+    out = torch.full((8 * 256,), float("nan"), dtype=torch.float32, device="cuda")
+    flops = m.maskkv_probe(0, 10, None, out, 8)
+    torch.cuda.synchronize()
+    assert flops == 8 * 4 * 4 * 10 * 32768.0 and bool(torch.isfinite(out).all())
+    out.fill_(float("nan"))
+    n_exp = m.maskkv_probe(1, 10, None, out, 8)
+    torch.cuda.synchronize()
+    assert n_exp == 8 * 256 * 8 * 10 and bool(((out > 0) & (out <= 8)).all())      # eight values in (0, 1] per lane
+    src = torch.arange(100003 * 4, dtype=torch.int32, device="cuda")               # a ragged number of 16-byte pieces
+    dst = torch.zeros_like(src)
+    moved = m.maskkv_probe(2, 0, src, dst, 7)
+    torch.cuda.synchronize()
+    assert moved == 2.0 * src.numel() * 4 and torch.equal(src, dst)
+    words = torch.zeros(7 * 256, dtype=torch.int32, device="cuda")
+    assert m.maskkv_probe(3, 0, src, words, 7) == src.numel() * 4
+    torch.cuda.synchronize()
+    fold = 0
+    for v in src.cpu().numpy().tolist():
+        fold ^= v
+    got = 0
+    for v in words.cpu().numpy().tolist():
+        got ^= v & 0xFFFFFFFF
+    assert got == fold                                                             # every word was read once
