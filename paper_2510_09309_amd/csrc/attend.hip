@@ -2,8 +2,8 @@
 // (MaskKV Section 3.1 layer forward equation; appendix: AttnOut_m = sum_j alpha_mj V_j), and the
 // same attention over the un-evicted sequence.
 //
-// Flash-style single pass with an online softmax.  One workgroup = 4 waves = 128 queries of one (b, h);
-// each wave owns 32 queries.  The logits are formed transposed (keys on the MFMA row axis, queries on
+// Flash-style single pass with an online softmax.  One workgroup = 8 waves = 256 queries of one (b, h)
+// sharing every staged K/V tile (4 waves at bf16 head_dim 64); each wave owns 32 queries.  The logits are formed transposed (keys on the MFMA row axis, queries on
 // the column axis), so a lane owns one query: its running max / sum stay in the lane and the
 // probabilities it holds are already laid out as the B operand of O^T = V^T P^T.  V tiles are written
 // to LDS transposed so that the A operand of that product is read with 8/16-byte LDS loads.
@@ -15,9 +15,9 @@ namespace maskkv {
 
 namespace {
 
-constexpr int kAttThreads = 256;
+constexpr int kAttThreads = 256;  // narrow kernel
 constexpr int kAttWaves = 4;
-constexpr int kQPerBlock = kAttWaves * 32;
+constexpr int kNarrowBelow = 256;  // launches of fewer 128-query tiles than this take the narrow kernel
 constexpr float kLazyBump = 8.f;  // log2 of the largest probability tolerated before the running reference is raised
 
 template <typename T, int D>
@@ -28,7 +28,12 @@ struct AttCfg {
   static constexpr int kTK = (kRowB <= 256) ? 64 : 32;
   static constexpr int kNKB = kTK / 32;
   static constexpr int kPiecesPerRow = kRowB / 16;
-  static constexpr int kPieces = kTK * kRowB / 16 / kAttThreads;
+  // Waves (32 queries each) that share a K/V tile: eight where a thread still moves whole 16-byte pieces of K
+  // and pairs of V rows, i.e. everywhere but bf16 at head_dim 64.
+  static constexpr int kWaves = (sizeof(T) == 2 && D == 64) ? 4 : 8;
+  static constexpr int kThreads = kWaves * 64;
+  static constexpr int kQPerBlock = kWaves * 32;
+  static constexpr int kPieces = kTK * kRowB / 16 / kThreads;
   static constexpr int kSV = kTK + 4;  // elements per transposed-V row (padding keeps LDS reads conflict-free)
   static constexpr int kDB = D / 32;
 };
@@ -62,7 +67,7 @@ __device__ __forceinline__ void load_kv(const AttendParams& prm, const KeySpace&
   using C = AttCfg<T, D>;
 #pragma unroll
   for (int i = 0; i < C::kPieces; ++i) {
-    const int p = threadIdx.x + i * kAttThreads;
+    const int p = threadIdx.x + i * C::kThreads;
     {
       const int row = p / C::kPiecesPerRow, col = p % C::kPiecesPerRow;
       const int j = min(key0 + row, klast);
@@ -72,7 +77,7 @@ __device__ __forceinline__ void load_kv(const AttendParams& prm, const KeySpace&
     {
       int row, col;
       if (sizeof(T) == 2) {  // item = (key pair, 16-byte slice); pieces 2i and 2i+1 are the pair's two rows
-        const int item = threadIdx.x + (i / 2) * kAttThreads;
+        const int item = threadIdx.x + (i / 2) * C::kThreads;
         row = 2 * (item / C::kPiecesPerRow) + (i & 1);
         col = item % C::kPiecesPerRow;
       } else {
@@ -92,7 +97,7 @@ __device__ __forceinline__ void store_kv(char* kt, char* vt, const u32x4 (&kr)[A
   using C = AttCfg<T, D>;
 #pragma unroll
   for (int i = 0; i < C::kPieces; ++i) {
-    const int p = threadIdx.x + i * kAttThreads;
+    const int p = threadIdx.x + i * C::kThreads;
     const int row = p / C::kPiecesPerRow, col = p % C::kPiecesPerRow;
     *reinterpret_cast<u32x4*>(kt + row * C::kRowP + col * 16) = kr[i];
   }
@@ -101,7 +106,7 @@ __device__ __forceinline__ void store_kv(char* kt, char* vt, const u32x4 (&kr)[A
     // vt[e][key] as bf16: a 32-bit word holds keys (2*pair, 2*pair+1) of one head-dim element
 #pragma unroll
     for (int i = 0; i < C::kPieces / 2; ++i) {
-      const int item = threadIdx.x + i * kAttThreads;
+      const int item = threadIdx.x + i * C::kThreads;
       const int pair = item / C::kPiecesPerRow, col = item % C::kPiecesPerRow;
       const u32x4 a = vr[2 * i], bq = vr[2 * i + 1];
 #pragma unroll
@@ -116,7 +121,7 @@ __device__ __forceinline__ void store_kv(char* kt, char* vt, const u32x4 (&kr)[A
   } else {
 #pragma unroll
     for (int i = 0; i < C::kPieces; ++i) {
-      const int p = threadIdx.x + i * kAttThreads;
+      const int p = threadIdx.x + i * C::kThreads;
       const int row = p / C::kPiecesPerRow, col = p % C::kPiecesPerRow;
 #pragma unroll
       for (int w = 0; w < 4; ++w) vt32[(col * 4 + w) * C::kSV + row] = vr[i][w];
@@ -125,7 +130,7 @@ __device__ __forceinline__ void store_kv(char* kt, char* vt, const u32x4 (&kr)[A
 }
 
 template <typename T, int D>
-__global__ __launch_bounds__(kAttThreads) void attend_kernel(const AttendParams prm) {
+__global__ __launch_bounds__((AttCfg<T, D>::kThreads)) void attend_kernel(const AttendParams prm) {
   using C = AttCfg<T, D>;
   __shared__ __attribute__((aligned(16))) char kt[C::kTK * C::kRowP];
   __shared__ __attribute__((aligned(16))) char vt[D * C::kSV * sizeof(T)];
@@ -133,7 +138,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const AttendParams 
   // Workgroup numbers that are congruent modulo 8 run on the same XCD and share its L2.  The query tiles of
   // one (head, key split) read the same K/V rows, so they are given consecutive slots of one XCD: the rows
   // then come from HBM once instead of once per query tile.
-  const int qtiles = (prm.n_q + kQPerBlock - 1) / kQPerBlock;
+  const int qtiles = (prm.n_q + C::kQPerBlock - 1) / C::kQPerBlock;
   const int slot = blockIdx.x / 8;
   const int unit = (slot / qtiles) * 8 + blockIdx.x % 8;  // (head, split) pair
   const int qtile = slot % qtiles;
@@ -166,7 +171,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(const AttendParams 
   const int j1 = min(Lk, j0 + Ls);
   const int ntiles = j1 > j0 ? (j1 - j0 + C::kTK - 1) / C::kTK : 0;
 
-  const int q = qtile * kQPerBlock + wave * 32 + r;
+  const int q = qtile * C::kQPerBlock + wave * 32 + r;
   u32x4 qf[C::kSteps];
 #pragma unroll
   for (int s = 0; s < C::kSteps; ++s) {
@@ -561,11 +566,16 @@ __global__ __launch_bounds__(256) void attend_merge_kernel(const AttendParams pr
   if (prm.lse && e == 0) prm.lse[(int64_t)bh * prm.n_q + q] = (M + __log2f(L)) * kLn2;
 }
 
+// Queries per workgroup of the tiled kernel for this description.
+int tiled_queries(const maskkv_desc* d) {
+  return (d->dtype == MASKKV_BF16 && d->d == 64) ? AttCfg<bf16_t, 64>::kQPerBlock : AttCfg<bf16_t, 128>::kQPerBlock;
+}
+
 int attend_splits(const maskkv_desc* d, bool full) {
   if (!full) return 1;
-  const int64_t qtiles = ((int64_t)d->n_resp * query_heads_per_kv(d) + kQPerBlock - 1) / kQPerBlock;
+  const int64_t qtiles = ((int64_t)d->n_resp * query_heads_per_kv(d) + tiled_queries(d) - 1) / tiled_queries(d);
   const int64_t blocks = qtiles * d->B * d->H;
-  int64_t s = (512 + blocks - 1) / blocks;  // about two workgroups per compute unit (measured best)
+  int64_t s = (256 + blocks - 1) / blocks;  // one workgroup per compute unit, a single round (measured best)
   const int64_t by_len = ((int64_t)d->P_max + d->n_resp + 511) / 512;
   if (s > by_len) s = by_len;
   if (s > 64) s = 64;
@@ -576,8 +586,8 @@ int attend_splits(const maskkv_desc* d, bool full) {
 // The narrow kernel is used when the tiled kernel would launch fewer workgroups than there are compute units.
 bool attend_is_narrow(const maskkv_desc* d, bool full) {
   if (full || d->dtype != MASKKV_BF16) return false;
-  const int64_t qtiles = ((int64_t)d->n_resp * query_heads_per_kv(d) + kQPerBlock - 1) / kQPerBlock;
-  return qtiles * d->B * d->H < 256;
+  const int64_t qtiles = ((int64_t)d->n_resp * query_heads_per_kv(d) + 127) / 128;
+  return qtiles * d->B * d->H < kNarrowBelow;
 }
 
 template <int D>
@@ -602,13 +612,14 @@ int launch_attend_narrow(const AttendParams& prm, hipStream_t stream) {
 
 template <typename T, int D>
 int launch_attend_t(const AttendParams& prm, int B, hipStream_t stream) {
-  const int64_t qtiles = (prm.n_q + kQPerBlock - 1) / kQPerBlock;
+  using C = AttCfg<T, D>;
+  const int64_t qtiles = (prm.n_q + C::kQPerBlock - 1) / C::kQPerBlock;
   const int64_t units = ((int64_t)B * prm.H * prm.n_splits + 7) / 8 * 8;  // (head, split) pairs, whole rounds of XCDs
   if (units * qtiles > 0x7FFFFFFF) {
     set_error("attend: %lld workgroups exceed the launch limit", (long long)(units * qtiles));
     return MASKKV_ESHAPE;
   }
-  hipLaunchKernelGGL((attend_kernel<T, D>), dim3((unsigned)(units * qtiles)), dim3(kAttThreads), 0, stream, prm);
+  hipLaunchKernelGGL((attend_kernel<T, D>), dim3((unsigned)(units * qtiles)), dim3(C::kThreads), 0, stream, prm);
   if (int e = check_launch("attend")) return e;
   if (prm.n_splits > 1) {
     constexpr int kRows = 256 / (D / 4);
