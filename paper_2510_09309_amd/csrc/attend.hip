@@ -36,6 +36,9 @@ struct AttCfg {
   static constexpr int kPieces = kTK * kRowB / 16 / kThreads;
   static constexpr int kSV = kTK + 4;  // elements per transposed-V row (padding keeps LDS reads conflict-free)
   static constexpr int kDB = D / 32;
+  static constexpr int kKtBytes = kTK * kRowP;
+  static constexpr int kVtBytes = D * kSV * (int)sizeof(T);
+  static constexpr int kLds = 2 * (kKtBytes + kVtBytes);  // K and V^T tiles, double-buffered
 };
 
 struct AttendParams {
@@ -132,8 +135,7 @@ __device__ __forceinline__ void store_kv(char* kt, char* vt, const u32x4 (&kr)[A
 template <typename T, int D>
 __global__ __launch_bounds__((AttCfg<T, D>::kThreads)) void attend_kernel(const AttendParams prm) {
   using C = AttCfg<T, D>;
-  __shared__ __attribute__((aligned(16))) char kt[C::kTK * C::kRowP];
-  __shared__ __attribute__((aligned(16))) char vt[D * C::kSV * sizeof(T)];
+  extern __shared__ __attribute__((aligned(16))) char att_lds[];  // two buffers of (K tile, V^T tile)
 
   // Workgroup numbers that are congruent modulo 8 run on the same XCD and share its L2.  The query tiles of
   // one (head, key split) read the same K/V rows, so they are given consecutive slots of one XCD: the rows
@@ -190,15 +192,25 @@ __global__ __launch_bounds__((AttCfg<T, D>::kThreads)) void attend_kernel(const 
   // Two tiles are kept in flight in two register sets (a key axis of a few hundred rows is a short serial
   // chain of tiles, so the memory latency of each request has to hide behind two tiles of arithmetic).
   u32x4 kra[C::kPieces], vra[C::kPieces], krb[C::kPieces], vrb[C::kPieces];
+  // Tile t is computed from LDS buffer t&1 while tile t+1 is written to the other one: one barrier per tile.
   if (ntiles > 0) load_kv<T, D>(prm, ks, b, h, j0, j1 - 1, kra, vra);
   if (ntiles > 1) load_kv<T, D>(prm, ks, b, h, j0 + C::kTK, j1 - 1, krb, vrb);
+  if (ntiles > 0) {
+    store_kv<T, D>(att_lds, att_lds + C::kKtBytes, kra, vra);
+    if (ntiles > 2) load_kv<T, D>(prm, ks, b, h, j0 + 2 * C::kTK, j1 - 1, kra, vra);
+  }
+  __syncthreads();
 
+  // `kr`, `vr` hold tile t+1 on entry (if there is one) and are refilled with tile t+3.
   auto tile_step = [&](int t, u32x4 (&kr)[C::kPieces], u32x4 (&vr)[C::kPieces]) {
     const int key0 = j0 + t * C::kTK;
-    __syncthreads();  // the previous tile's readers are done
-    store_kv<T, D>(kt, vt, kr, vr);
-    __syncthreads();
-    if (t + 2 < ntiles) load_kv<T, D>(prm, ks, b, h, key0 + 2 * C::kTK, j1 - 1, kr, vr);
+    const char* kt = att_lds + (t & 1) * (C::kKtBytes + C::kVtBytes);
+    const char* vt = kt + C::kKtBytes;
+    if (t + 1 < ntiles) {  // the other buffer's readers (tile t-1) passed the barrier that ended the previous step
+      char* nk = att_lds + ((t + 1) & 1) * (C::kKtBytes + C::kVtBytes);
+      store_kv<T, D>(nk, nk + C::kKtBytes, kr, vr);
+      if (t + 3 < ntiles) load_kv<T, D>(prm, ks, b, h, key0 + 3 * C::kTK, j1 - 1, kr, vr);
+    }
 
     // S^T = K Q^T for this tile
     f32x16 s[C::kNKB];
@@ -288,10 +300,11 @@ __global__ __launch_bounds__((AttCfg<T, D>::kThreads)) void attend_kernel(const 
           }
         }
     }
+    __syncthreads();  // tile t+1 is visible; every wave is done with tile t
   };
   for (int t = 0; t < ntiles; t += 2) {
-    tile_step(t, kra, vra);
-    if (t + 1 < ntiles) tile_step(t + 1, krb, vrb);
+    tile_step(t, krb, vrb);
+    if (t + 1 < ntiles) tile_step(t + 1, kra, vra);
   }
 
   const float l_tot = l + xor32(l);
@@ -619,7 +632,19 @@ int launch_attend_t(const AttendParams& prm, int B, hipStream_t stream) {
     set_error("attend: %lld workgroups exceed the launch limit", (long long)(units * qtiles));
     return MASKKV_ESHAPE;
   }
-  hipLaunchKernelGGL((attend_kernel<T, D>), dim3((unsigned)(units * qtiles)), dim3(C::kThreads), 0, stream, prm);
+  static bool raised = false;  // one-time opt-in to more than the default dynamic LDS size
+  if (C::kLds > 48 * 1024 && !raised) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_kernel<T, D>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, C::kLds);
+    if (e != hipSuccess) {
+      set_error("attend: cannot raise dynamic LDS limit: %s", hipGetErrorString(e));
+      (void)hipGetLastError();
+      return MASKKV_EHIP;
+    }
+    raised = true;
+  }
+  hipLaunchKernelGGL((attend_kernel<T, D>), dim3((unsigned)(units * qtiles)), dim3(C::kThreads), C::kLds, stream,
+                     prm);
   if (int e = check_launch("attend")) return e;
   if (prm.n_splits > 1) {
     constexpr int kRows = 256 / (D / 4);
