@@ -122,3 +122,16 @@ def test_c5_shaped_ragged_batch_reduced():
         for h in (0, 3):
             I, _ = orc.score(L.Q[h], L.K[h], L.P)
             hp.check_keep_against_oracle(orc.pool(I, 7), int(budgets[b * H + h]), keeps[b * H + h], f"b{b} h{h}")
+
+
+@pytest.mark.parametrize("layer", [0, 1, 31])
+def test_c3_layers_with_the_layer_budget_schedule(layer):
+    """The 32-layer stack configuration (P = 8192): boundary layers keep 512 rows per head on average, the middle
+    layers 128; every step of layers 0, 1 and 31 is checked on sampled heads, the budget sums on all."""
+    from tests.test_gpu_parity import pipeline_parity
+    cfg = synth.CONFIGS["C3"]
+    budgets = synth.config_budgets("C3", layer)
+    assert budgets.sum() == 32 * (512 if layer in (0, 31) else 128)
+    batch = hp.Batch([synth.config_layer("C3", layer=layer)])
+    worst, n_band = pipeline_parity(batch, budgets, cfg["window"], heads=[0, 7, 20, 31])
+    assert worst < 1e-4
