@@ -454,21 +454,26 @@ __global__ __launch_bounds__(kAttThreads) void attend_narrow_kernel(const Attend
 #pragma unroll
     for (int i = 1; i < 16; ++i) bm = fmaxf(bm, s[i]);
     bm = fmaxf(bm, xor32(bm));
-    const float m_new = fmaxf(m, bm * c);
-    const float alpha = fast_exp2(m - m_new);
+    const float cand = bm * c;
+    const bool bump = cand > m + kLazyBump;  // the reference is raised lazily, as in the tiled kernel
+    if (__any(bump)) {
+      const float m_new = bump ? cand : m;
+      const float alpha = fast_exp2(m - m_new);
+      m = m_new;
+      l *= alpha;
+#pragma unroll
+      for (int db = 0; db < C::kDB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+    }
     float psum = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const float pv = fast_exp2(fmaf(s[i], c, -m_new));
+      const float pv = fast_exp2(fmaf(s[i], c, -m));
       s[i] = pv;
       psum += pv;
     }
-    l = l * alpha + psum;
-    m = m_new;
-#pragma unroll
-    for (int db = 0; db < C::kDB; ++db)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+    l += psum;
     // O^T += V^T P^T
 #pragma unroll
     for (int tp = 0; tp < 2; ++tp) {
