@@ -51,7 +51,8 @@ struct SelectParams {
 };
 
 __device__ __forceinline__ uint32_t order_key(float v) {
-  const uint32_t u = __builtin_bit_cast(uint32_t, v);
+  uint32_t u = __builtin_bit_cast(uint32_t, v);
+  if (u == 0x80000000u) u = 0u;                         // -0 and +0 compare equal: one key for both
   return u ^ ((u >> 31) ? 0xFFFFFFFFu : 0x80000000u);  // larger float <=> larger unsigned key
 }
 

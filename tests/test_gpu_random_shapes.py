@@ -49,3 +49,57 @@ def test_random_grouped_query_shapes(seed):
     budgets = [int(rng.choice([0, 3, 64, 200, 10 ** 6])) for _ in range(H)]
     run_grouped(seed=31_000 + seed, H=H, g=g, d=[64, 128][int(rng.integers(2))], P=P, n_m=n_m, dtype=dtype,
                 budgets=budgets, window=int(rng.choice([1, 7])))
+
+
+def score_family(kind, rng, P):
+    if kind == "few_values":
+        return rng.choice(np.array([0.0, 1e-7, 0.5, 0.5000001], dtype=np.float32), size=P)
+    if kind == "ascending":
+        return np.sort(rng.random(P).astype(np.float32))
+    if kind == "descending":
+        return np.sort(rng.random(P).astype(np.float32))[::-1].copy()
+    if kind == "negative_and_zero":
+        x = rng.standard_normal(P).astype(np.float32)
+        x[rng.random(P) < 0.3] = 0.0
+        x[rng.random(P) < 0.05] = -0.0
+        return x
+    if kind == "denormal":
+        return (rng.random(P) * 1e-41).astype(np.float32)
+    if kind == "huge_range":
+        return (10.0 ** rng.uniform(-30, 30, size=P)).astype(np.float32) * rng.choice([-1.0, 1.0], size=P).astype(np.float32)
+    if kind == "flat_with_spikes":
+        x = np.full(P, 7.6e-3, dtype=np.float32) * (1 + 1e-6 * rng.standard_normal(P)).astype(np.float32)
+        x[rng.choice(P, size=max(P // 100, 1), replace=False)] *= np.float32(40.0)
+        return x
+    raise ValueError(kind)
+
+
+@pytest.mark.parametrize("kind", ["few_values", "ascending", "descending", "negative_and_zero", "denormal",
+                                  "huge_range", "flat_with_spikes"])
+def test_select_on_adversarial_score_distributions(kind):
+    """select alone on given fp32 scores: every decision is made in fp32 on both sides, so the index lists are
+    identical - for ties, signed zeros, denormals, 60 decades of range, sorted inputs, and budgets on both sides of
+    the 4096-candidate list."""
+    import torch
+    from oracle import maskkv_oracle as orc
+    m = hp.mk()
+    rng = np.random.default_rng(sum(kind.encode()))
+    Ps = [4095, 4097, 8191, 12289, 33001]
+    budgets_per = [1, 300, 4096, 4097]
+    for window in (1, 7):
+        for P in Ps:
+            H = len(budgets_per)
+            desc = m.Desc(B=1, H=H, d=128, dtype=m.MASKKV_BF16, n_resp=8, P_max=P)
+            sc = np.stack([score_family(kind, rng, P) for _ in range(H)])
+            budgets = np.array([min(b, P) for b in budgets_per], dtype=np.int32)
+            budgets[-1] = min(P - 1, budgets[-1] + (P // 2 if P > 20000 else 0))      # a budget of half a long prompt
+            cap = int(budgets.sum())
+            idx = torch.full((cap,), -1, dtype=torch.int32, device="cuda")
+            cu = torch.zeros(H + 1, dtype=torch.int32, device="cuda")
+            m.maskkv_select(desc, torch.from_numpy(sc).to("cuda"), P, window, 0, torch.from_numpy(budgets).to("cuda"),
+                            idx, cu, cap, hp.workspace(m.maskkv_select_workspace_bytes(desc)))
+            torch.cuda.synchronize()
+            keeps, _ = hp.split_idx(idx, cu)
+            for h in range(H):
+                ref = orc.select(orc.pool(sc[h], window, "mean", dtype=np.float32), int(budgets[h]))
+                assert np.array_equal(keeps[h], ref), f"{kind} window {window} P {P} k {budgets[h]}"
