@@ -103,3 +103,28 @@ def test_select_on_adversarial_score_distributions(kind):
             for h in range(H):
                 ref = orc.select(orc.pool(sc[h], window, "mean", dtype=np.float32), int(budgets[h]))
                 assert np.array_equal(keeps[h], ref), f"{kind} window {window} P {P} k {budgets[h]}"
+
+
+@pytest.mark.parametrize("sigma,dtype", [(40.0, "bf16"), (80.0, "bf16"), (80.0, "f32")])
+def test_very_large_logits_stay_finite_and_accurate(sigma, dtype):
+    """Logits of magnitude 50-230 (exp would overflow fp32 without the running reference): scores stay finite and
+    within the score tolerance wherever fp32 can represent them (the float64 oracle goes down to 1e-200, fp32 output
+    underflows to zero there); the un-evicted attention stays within bf16 rounding of its value range."""
+    from oracle import maskkv_oracle as orc
+    L = synth.make_layer(77, H=2, d=128, P=1500, n_m=70, dtype=dtype, n_planted=10, amplitude=2.5, sigma=sigma)
+    batch = hp.Batch([L])
+    scores, mass = hp.gpu_score(batch)
+    sc = scores.cpu().numpy()
+    O, _ = hp.gpu_attend_full(batch)
+    for h in range(L.H):
+        I, m_ref = orc.score(L.Q[h], L.K[h], L.P)
+        got = sc[h, :L.P].astype(np.float64)
+        assert np.isfinite(got).all() and (got >= 0).all()
+        big = I > 1e-30
+        assert big.sum() > 1000
+        assert (np.abs(got[big] - I[big]) / I[big]).max() <= hp.SCORE_RTOL
+        assert (got[~big] <= 2e-30).all()
+        assert abs(mass[h].item() - m_ref) <= hp.SCORE_RTOL * m_ref
+        ref = orc.attend_full(L.Q[h], L.K[h], L.V[h])
+        atol = (hp.ATTEND_ATOL_BF16 if dtype == "bf16" else 1e-4) * max(1.0, float(np.abs(L.V[h]).max()))
+        assert np.abs(O[0, h].float().cpu().numpy() - ref).max() <= atol
