@@ -128,3 +128,67 @@ def test_very_large_logits_stay_finite_and_accurate(sigma, dtype):
         ref = orc.attend_full(L.Q[h], L.K[h], L.V[h])
         atol = (hp.ATTEND_ATOL_BF16 if dtype == "bf16" else 1e-4) * max(1.0, float(np.abs(L.V[h]).max()))
         assert np.abs(O[0, h].float().cpu().numpy() - ref).max() <= atol
+
+
+def test_packed_variable_length_layout():
+    """Sequences packed back to back on the token axis ([T_total, heads, d], batch stride 0, per-sequence token
+    offsets): the layout of variable-length attention libraries.  Every call of the path reads and writes it."""
+    import torch
+    from oracle import maskkv_oracle as orc
+    m = hp.mk()
+    H, d, n_m = 3, 128, 48
+    Ps = [700, 0, 1300]
+    B = len(Ps)
+    layers = [synth.make_layer(5000 + b, H=H, d=d, P=Ps[b], n_m=n_m, dtype="bf16", n_planted=min(8, Ps[b]),
+                               amplitude=2.5) for b in range(B)]
+    starts = np.concatenate([[0], np.cumsum([P + n_m for P in Ps])]).astype(int)
+    T = int(starts[-1])
+    Kp = np.zeros((T, H, d), dtype=np.float32)
+    Vp = np.zeros_like(Kp)
+    Qp = np.zeros((B * n_m, H, d), dtype=np.float32)
+    for b, L in enumerate(layers):
+        Kp[starts[b]:starts[b + 1]] = L.K.transpose(1, 0, 2)
+        Vp[starts[b]:starts[b + 1]] = L.V.transpose(1, 0, 2)
+        Qp[b * n_m:(b + 1) * n_m] = L.Q.transpose(1, 0, 2)
+    packed = lambda x: hp.upload(x, "bf16").permute(1, 0, 2)[None].expand(B, -1, -1, -1)   # [B, H, T, d], stride_b = 0
+    K, V, Q = packed(Kp), packed(Vp), packed(Qp)
+    assert K.stride(0) == 0 and K.stride(1) == d and K.stride(2) == H * d
+    kv_start = [int(s) for s in starts[:-1]]
+    q_start = [b * n_m for b in range(B)]
+    Kv, Vv, Qv = m.tensor_view(K, kv_start), m.tensor_view(V, kv_start), m.tensor_view(Q, q_start)
+    desc = m.Desc(B=B, H=H, d=d, dtype=m.MASKKV_BF16, n_resp=n_m, P_max=max(Ps), prompt_len=Ps)
+    stride = (max(Ps) + 63) // 64 * 64
+    scores = torch.full((B * H, stride), float("nan"), dtype=torch.float32, device="cuda")
+    mass = torch.zeros(B * H, dtype=torch.float32, device="cuda")
+    m.maskkv_score(desc, Qv, Kv, 0.0, scores, stride, mass, hp.workspace(m.maskkv_score_workspace_bytes(desc)))
+    budgets = np.array([100, 7, 700, 5, 5, 5, 64, 1300, 0], dtype=np.int32)
+    clamped = [min(int(budgets[i]), Ps[i // H]) for i in range(B * H)]
+    cap = sum(clamped)
+    idx = torch.full((cap,), -1, dtype=torch.int32, device="cuda")
+    cu = torch.zeros(B * H + 1, dtype=torch.int32, device="cuda")
+    m.maskkv_select(desc, scores, stride, 7, 0, torch.from_numpy(budgets).cuda(), idx, cu, cap,
+                    hp.workspace(m.maskkv_select_workspace_bytes(desc)))
+    Kc = torch.zeros((cap, d), dtype=torch.bfloat16, device="cuda")
+    Vc = torch.zeros_like(Kc)
+    m.maskkv_compact(desc, Kv, Vv, idx, cu, cap, Kc, Vc)
+    Op = torch.full((B * n_m, H, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    Ov = m.tensor_view(Op.permute(1, 0, 2)[None].expand(B, -1, -1, -1), q_start)
+    resp_start = [int(starts[b] + Ps[b]) for b in range(B)]
+    m.maskkv_attend(desc, Qv, Kc, Vc, cu, cap, m.tensor_view(K, resp_start), m.tensor_view(V, resp_start), 0.0, Ov,
+                    None, hp.workspace(m.maskkv_attend_workspace_bytes(desc, False)))
+    torch.cuda.synchronize()
+    keeps, cu_h = hp.split_idx(idx, cu)
+    sc = scores.cpu().numpy()
+    O_h = Op.float().cpu().numpy()
+    assert np.isfinite(O_h).all()
+    for b, L in enumerate(layers):
+        for h in range(H):
+            bh = b * H + h
+            keep = keeps[bh]
+            if L.P:
+                I, _ = orc.score(L.Q[h], L.K[h], L.P)
+                assert (np.abs(sc[bh, :L.P] - I) / I).max() <= hp.SCORE_RTOL
+                hp.check_keep_against_oracle(orc.pool(I, 7), clamped[bh], keep, f"b{b} h{h}")
+            assert np.array_equal(Kc.float().cpu().numpy()[cu_h[bh]:cu_h[bh + 1]], L.K[h, keep])
+            ref = orc.attend(L.Q[h], L.K[h, keep], L.V[h, keep], L.K[h, L.P:], L.V[h, L.P:])
+            assert np.abs(O_h[b * n_m:(b + 1) * n_m, h] - ref).max() <= hp.ATTEND_ATOL_BF16
