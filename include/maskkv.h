@@ -206,7 +206,8 @@ int maskkv_attend_full(const maskkv_desc* desc, const maskkv_tensor* Q_resp,
  *   P_h = prompt_mass[b*H+h] / (g*n_query)  (mask-to-prompt share of the voting rows' attention)
  *   budgets[b*H+h] = floor(alpha*k_l + (1-alpha) * H * k_l * P_h / sum_h' P_h')
  * prompt_mass: DEVICE float [B*H] as written by maskkv_score; budgets: DEVICE int32 [B*H].
- * k_l is the layer's per-head average budget; 0 <= alpha <= 1.
+ * k_l is the layer's per-head average budget; 0 <= alpha <= 1.  A sequence whose masses are all zero (empty
+ * prompt) gets budgets[..] = k_l for every head.
  */
 int maskkv_head_budgets(const maskkv_desc* desc, const float* prompt_mass, int32_t k_l, float alpha,
                         int32_t* budgets, void* stream);

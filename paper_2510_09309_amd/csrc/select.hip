@@ -451,7 +451,8 @@ __global__ __launch_bounds__(256) void head_budgets_kernel(const BudgetParams pr
   }
   const float total = red[0];
   for (int h = threadIdx.x; h < prm.H; h += 256) {
-    const float p_hat = (prm.mass[b * prm.H + h] / (float)prm.n_query) / total;
+    // a sequence without any prompt mass (empty prompt) has no preference: every head gets k_l
+    const float p_hat = total > 0.f ? (prm.mass[b * prm.H + h] / (float)prm.n_query) / total : 1.f / (float)prm.H;
     const float v = prm.alpha * (float)prm.k_l + (1.f - prm.alpha) * (float)prm.H * (float)prm.k_l * p_hat;
     prm.budgets[b * prm.H + h] = (int32_t)floorf(v);
   }

@@ -265,6 +265,28 @@ def test_head_budgets_on_device():
     assert cu.cpu().numpy().tolist() == np.concatenate([[0], np.cumsum(got)]).tolist()
 
 
+def test_head_budgets_batch_with_an_empty_prompt_and_many_heads():
+    """Per-sequence normalisation over more heads than one pass of the workgroup covers; a sequence without a prompt
+    (all masses zero) gets the uniform budget."""
+    m = hp.mk()
+    B, H, k_l, alpha = 3, 300, 100, 0.25
+    rng = np.random.default_rng(12)
+    mass_h = rng.random((B, H)).astype(np.float32) * 50
+    mass_h[1] = 0.0
+    desc = m.Desc(B=B, H=H, d=64, dtype=m.MASKKV_BF16, n_resp=64, P_max=128, prompt_len=[128, 0, 77])
+    bud = torch.full((B * H,), -1, dtype=torch.int32, device="cuda")
+    m.maskkv_head_budgets(desc, torch.from_numpy(mass_h.reshape(-1)).cuda(), k_l, alpha, bud)
+    torch.cuda.synchronize()
+    got = bud.cpu().numpy().reshape(B, H)
+    assert (got[1] == k_l).all()
+    for b in (0, 2):
+        pref = orc.prompt_preference(mass_h[b].astype(np.float64), 64)
+        exact = alpha * k_l + (1 - alpha) * H * k_l * pref / pref.sum()
+        near_int = np.abs(exact - np.rint(exact)) < 1e-2
+        assert np.all((got[b] == orc.head_budgets(pref, k_l, alpha)) | near_int)
+        assert got[b].sum() <= H * k_l
+
+
 def test_full_budget_compressed_equals_full_attention_on_gpu():
     """Nothing evicted: attend over the compacted cache must agree with attend_full (same kernel family)."""
     L = synth.make_layer(82, H=2, d=128, P=900, n_m=130, dtype="bf16", n_planted=10, amplitude=2.5)
