@@ -192,3 +192,59 @@ def test_packed_variable_length_layout():
             assert np.array_equal(Kc.float().cpu().numpy()[cu_h[bh]:cu_h[bh + 1]], L.K[h, keep])
             ref = orc.attend(L.Q[h], L.K[h, keep], L.V[h, keep], L.K[h, L.P:], L.V[h, L.P:])
             assert np.abs(O_h[b * n_m:(b + 1) * n_m, h] - ref).max() <= hp.ATTEND_ATOL_BF16
+
+
+def test_maximum_batch_of_64_ragged_sequences():
+    """MASKKV_MAX_BATCH sequences in one call, prompts from empty to a few hundred tokens."""
+    rng = np.random.default_rng(64)
+    B, H = 64, 2
+    Ps = [int(p) for p in rng.integers(0, 400, size=B)]
+    Ps[0], Ps[63] = 399, 0
+    layers = [synth.make_layer(7000 + b, H=H, d=64, P=Ps[b], n_m=33, dtype="bf16", n_planted=min(3, Ps[b]),
+                               amplitude=2.5) for b in range(B)]
+    batch = hp.Batch(layers)
+    budgets = rng.integers(0, 120, size=B * H).astype(np.int32)
+    worst, _ = pipeline_parity(batch, budgets, 7, heads=[0, 1])
+    assert worst <= hp.SCORE_RTOL
+
+
+def test_largest_supported_token_stride():
+    """Rows 16 MiB apart (the documented limit): one head, 40 prompt + 24 response tokens spread over 1 GiB."""
+    import torch
+    from oracle import maskkv_oracle as orc
+    m = hp.mk()
+    d, P, n_m = 128, 40, 24
+    N = P + n_m
+    stride_t = (16 << 20) // 2                      # elements of bf16
+    L = synth.make_layer(7100, H=1, d=d, P=P, n_m=n_m, dtype="bf16", n_planted=4, amplitude=2.5)
+    big = [torch.zeros((N - 1) * stride_t + d, dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+    views = []
+    for buf, src in zip(big, (L.K[0], L.V[0])):
+        v = torch.as_strided(buf, (1, 1, N, d), (0, 0, stride_t, 1))
+        v.copy_(hp.upload(src, "bf16")[None, None])
+        views.append(v)
+    K, V = views
+    Q = hp.upload(L.Q[None], "bf16")
+    desc = m.Desc(B=1, H=1, d=d, dtype=m.MASKKV_BF16, n_resp=n_m, P_max=P)
+    scores = torch.zeros((1, 64), dtype=torch.float32, device="cuda")
+    m.maskkv_score(desc, Q, K, 0.0, scores, 64, None, hp.workspace(m.maskkv_score_workspace_bytes(desc)))
+    idx = torch.zeros(10, dtype=torch.int32, device="cuda")
+    cu = torch.zeros(2, dtype=torch.int32, device="cuda")
+    m.maskkv_select(desc, scores, 64, 1, 0, torch.tensor([10], dtype=torch.int32, device="cuda"), idx, cu, 10,
+                    hp.workspace(m.maskkv_select_workspace_bytes(desc)))
+    Kc = torch.zeros((10, d), dtype=torch.bfloat16, device="cuda")
+    Vc = torch.zeros_like(Kc)
+    m.maskkv_compact(desc, K, V, idx, cu, 10, Kc, Vc)
+    O = torch.zeros((1, 1, n_m, d), dtype=torch.bfloat16, device="cuda")
+    m.maskkv_attend(desc, Q, Kc, Vc, cu, 10, m.tensor_view(K, [P]), m.tensor_view(V, [P]), 0.0, O, None, None)
+    O2 = torch.zeros_like(O)
+    m.maskkv_attend_full(desc, Q, K, V, 0.0, O2, None, hp.workspace(m.maskkv_attend_workspace_bytes(desc, True)))
+    torch.cuda.synchronize()
+    I, _ = orc.score(L.Q[0], L.K[0], P)
+    assert (np.abs(scores[0, :P].cpu().numpy() - I) / I).max() <= hp.SCORE_RTOL
+    keep = idx.cpu().numpy()
+    hp.check_keep_against_oracle(I, 10, keep, "16 MiB stride")
+    assert np.array_equal(Kc.float().cpu().numpy(), L.K[0, keep])
+    ref = orc.attend(L.Q[0], L.K[0, keep], L.V[0, keep], L.K[0, P:], L.V[0, P:])
+    assert np.abs(O[0, 0].float().cpu().numpy() - ref).max() <= hp.ATTEND_ATOL_BF16
+    assert np.abs(O2[0, 0].float().cpu().numpy() - orc.attend_full(L.Q[0], L.K[0], L.V[0])).max() <= hp.ATTEND_ATOL_BF16
