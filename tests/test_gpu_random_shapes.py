@@ -248,3 +248,12 @@ def test_largest_supported_token_stride():
     ref = orc.attend(L.Q[0], L.K[0, keep], L.V[0, keep], L.K[0, P:], L.V[0, P:])
     assert np.abs(O[0, 0].float().cpu().numpy() - ref).max() <= hp.ATTEND_ATOL_BF16
     assert np.abs(O2[0, 0].float().cpu().numpy() - orc.attend_full(L.Q[0], L.K[0], L.V[0])).max() <= hp.ATTEND_ATOL_BF16
+
+
+def test_very_long_prompt():
+    """A 200k-token prompt: thousands of key tiles per head, 49 select chunks read in place, one budget far beyond
+    the candidate list."""
+    L = synth.make_layer(7200, H=2, d=128, P=200_003, n_m=40, dtype="bf16", n_planted=500, amplitude=2.5)
+    batch = hp.Batch([L])
+    worst, _ = pipeline_parity(batch, np.array([5000, 100_000], dtype=np.int32), 7)
+    assert worst <= hp.SCORE_RTOL
