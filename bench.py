@@ -340,7 +340,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures the hot path on ONE GPU; --gpus must be 1 "
-              "(the path is independent per head and needs no collective, see DESIGN.md)", file=sys.stderr)
+              "(the path is independent per head and would shard over heads or sequences without any collective)", file=sys.stderr)
         sys.exit(2)
 
     import torch
