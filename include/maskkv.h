@@ -175,7 +175,9 @@ int maskkv_compact(const maskkv_desc* desc, const maskkv_tensor* K, const maskkv
                    const int32_t* idx, const int32_t* cu_budget, int64_t capacity,
                    void* Kc, void* Vc, void* stream);
 
-/* Workspace (DEVICE bytes) for maskkv_attend / maskkv_attend_full (key-split partial results). */
+/* Workspace (DEVICE bytes) for maskkv_attend (full = 0: the order in which the heads are processed, longest key
+ * axis first; 0 for small launches) or maskkv_attend_full (full = 1: key-split partial results).  256-byte
+ * alignment. */
 int maskkv_attend_workspace_bytes(const maskkv_desc* desc, int full, size_t* bytes);
 
 /*

@@ -55,6 +55,7 @@ struct AttendParams {
   int n_q;       // query rows per key/value head = q_per_kv * n_resp
   float c;  // scale * log2(e)
   float* lse;
+  const int32_t* order;  // [BH] heads by descending key count (compressed call of the tiled kernel), or null
   float* part_o;     // [BH][n_splits][n_q][D]
   float2* part_ml;   // [BH][n_splits][n_q]
 };
@@ -147,8 +148,8 @@ __global__ __launch_bounds__((AttCfg<T, D>::kThreads)) void attend_kernel(const 
   const int unit = (slot / qtiles) * 8 + blockIdx.x % 8;  // (head, split) pair
   const int qtile = slot % qtiles;
   if (unit >= prm.BH * prm.n_splits) return;
-  const int bh = unit / prm.n_splits;
-  const int split = unit % prm.n_splits;
+  const int bh = prm.order ? prm.order[unit] : unit / prm.n_splits;  // (an order is only given without splits)
+  const int split = prm.order ? 0 : unit % prm.n_splits;
   const int b = bh / prm.H;
   const int h = bh % prm.H;
   const int lane = threadIdx.x & 63;
@@ -586,6 +587,45 @@ __global__ __launch_bounds__(256) void attend_merge_kernel(const AttendParams pr
   if (prm.lse && e == 0) prm.lse[(int64_t)bh * prm.n_q + q] = (M + __log2f(L)) * kLn2;
 }
 
+// Heads by descending key count, for the compressed call of the tiled kernel: budgets are ragged, the hardware
+// hands workgroups to compute units in launch order, and the longest heads should not start last (measured
+// on 256 heads with 576...1536 keys: 101 us in this order, 123 us in the given order).  A counting sort by
+// 64-key tile count in one workgroup; the order inside a bucket is whatever the atomics give, which does not
+// matter: every head's result is independent of when it runs.
+constexpr int kOrderThreads = 1024;
+constexpr int kOrderBuckets = 1024;
+
+__global__ __launch_bounds__(kOrderThreads) void attend_order_kernel(const int32_t* cu, int64_t capacity, int BH,
+                                                                     int n_resp, int32_t* order) {
+  __shared__ int count[kOrderBuckets];
+  __shared__ int wave_total[kOrderThreads / 64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  auto bucket_of = [&](int bh) {
+    const int64_t c0 = min((int64_t)cu[bh], capacity), c1 = min((int64_t)cu[bh + 1], capacity);
+    const int64_t tiles = (c1 - c0 + n_resp + 63) / 64;
+    return kOrderBuckets - 1 - (int)min((int64_t)(kOrderBuckets - 1), tiles);  // bucket 0 = longest
+  };
+  count[tid] = 0;
+  __syncthreads();
+  for (int bh = tid; bh < BH; bh += kOrderThreads) atomicAdd(&count[bucket_of(bh)], 1);
+  __syncthreads();
+  // exclusive prefix sum over the buckets, one bucket per thread
+  const int mine = count[tid];
+  int incl = mine;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int n = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += n;
+  }
+  if (lane == 63) wave_total[wave] = incl;
+  __syncthreads();
+  int before = 0;
+  for (int w = 0; w < wave; ++w) before += wave_total[w];
+  count[tid] = before + incl - mine;  // first slot of this bucket
+  __syncthreads();
+  for (int bh = tid; bh < BH; bh += kOrderThreads) order[atomicAdd(&count[bucket_of(bh)], 1)] = bh;
+}
+
 // Queries per workgroup of the tiled kernel for this description.
 int tiled_queries(const maskkv_desc* d) {
   return (d->dtype == MASKKV_BF16 && d->d == 64) ? AttCfg<bf16_t, 64>::kQPerBlock : AttCfg<bf16_t, 128>::kQPerBlock;
@@ -639,6 +679,11 @@ int launch_attend_t(const AttendParams& prm, int B, hipStream_t stream) {
     set_error("attend: %lld workgroups exceed the launch limit", (long long)(units * qtiles));
     return MASKKV_ESHAPE;
   }
+  if (prm.order) {
+    hipLaunchKernelGGL(attend_order_kernel, dim3(1), dim3(kOrderThreads), 0, stream, prm.cu, prm.capacity, prm.BH,
+                       prm.n_resp, const_cast<int32_t*>(prm.order));
+    if (int e = check_launch("attend (order)")) return e;
+  }
   static bool raised = false;  // one-time opt-in to more than the default dynamic LDS size
   if (C::kLds > 48 * 1024 && !raised) {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_kernel<T, D>),
@@ -666,6 +711,7 @@ int launch_attend_t(const AttendParams& prm, int B, hipStream_t stream) {
 
 size_t attend_workspace_bytes(const maskkv_desc* d, bool full) {
   const int s = attend_splits(d, full);
+  if (!full) return attend_is_narrow(d, full) ? 0 : ((size_t)d->B * d->H * sizeof(int32_t) + 255) / 256 * 256;
   if (s == 1) return 0;
   const size_t rows = (size_t)d->B * d->H * s * d->n_resp * query_heads_per_kv(d);
   return (rows * d->d * sizeof(float) + 255) / 256 * 256 + rows * sizeof(float2);
@@ -693,6 +739,7 @@ int launch_attend(const maskkv_desc* d, const Lens& lens, bool full, const View&
   prm.n_splits = attend_splits(d, full);
   prm.c = scale * kLog2e;
   prm.lse = lse;
+  prm.order = (!full && !attend_is_narrow(d, full)) ? reinterpret_cast<const int32_t*>(workspace) : nullptr;
   prm.part_o = nullptr;
   prm.part_ml = nullptr;
   if (prm.n_splits > 1) {
