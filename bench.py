@@ -253,12 +253,14 @@ def measured_peaks(torch, mk):
         return work * reps / (a.elapsed_time(b) * 1e-3)
     mfma = rate(lambda: mk.maskkv_probe(0, 20000, None, out, 512), 3)     # two waves per SIMD
     exps = rate(lambda: mk.maskkv_probe(1, 20000, None, out, 2048), 3)    # eight waves per SIMD
+    mix = rate(lambda: mk.maskkv_probe(4, 5000, None, out, 512), 3)       # two waves per SIMD, as score pass 2
     copy = rate(lambda: mk.maskkv_probe(2, 0, src, dst, 2048), 5)
     read = rate(lambda: mk.maskkv_probe(3, 0, src, out, 2048), 5)
     return {"mfma_bf16_tflops": mfma / 1e12, "v_exp_f32_per_s": exps, "stream_copy_gbs": copy / 1e9,
-            "stream_read_gbs": read / 1e9,
+            "stream_read_gbs": read / 1e9, "score_instruction_mix_tflops": mix / 1e12,
             "how": "maskkv_probe: register-only v_mfma_f32_32x32x16_bf16 loop on 512 workgroups, v_exp_f32 loop on "
-                   "2048 workgroups, 1 GiB copy (read + written bytes), 1 GiB read"}
+                   "2048 workgroups, 1 GiB copy (read + written bytes), 1 GiB read; instruction mix = 16 MFMAs + 32 x (fma, exp, "
+                   "add) per lane per iteration on 512 workgroups, no memory traffic"}
 
 
 def layer_importance_rate(torch, mk, n_tokens, hidden=4096):
@@ -483,6 +485,7 @@ def main():
         "frac_of_measured_mfma": out["roofline"]["achieved"] / peaks["mfma_bf16_tflops"],
         "mfma_time_us": flop_qk_all / (peaks["mfma_bf16_tflops"] * 1e12) * 1e6,
         "exp_time_us": n_exp / peaks["v_exp_f32_per_s"] * 1e6,
+        "instruction_mix_time_us": flop_qk_all / (peaks["score_instruction_mix_tflops"] * 1e12) * 1e6,
         "k_stream_time_us": bytes_k / (peaks["stream_read_gbs"] * 1e9) * 1e6,
         "measured_us": pass1_ms * 1e3}
     out["measured_peaks"] = peaks

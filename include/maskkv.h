@@ -262,6 +262,8 @@ int maskkv_value_shift(const void* V_now, const void* V_prev, int64_t n_tokens, 
  *   which = 1  v_exp_f32: every lane issues 8*iters exponentials;               *work = exponentials
  *   which = 2  streaming copy of `bytes` from src to dst (grid-stride, 16-byte pieces); *work = bytes read + written
  *   which = 3  streaming read of `bytes` from src (folded into one word per thread);     *work = bytes read
+ *   which = 4  the scoring kernels' instruction mix from registers: per iteration every wave issues 16 MFMAs and
+ *              every lane 32 x (fma, v_exp_f32, add);                    *work = floating-point operations of the MFMAs
  * dst: DEVICE of dst_bytes bytes; for which != 2 it receives groups*256 32-bit words, for which = 2 it is the copy
  * target.  src: DEVICE, 16-byte aligned, `bytes` a multiple of 16 (which >= 2; ignored otherwise).  work: HOST
  * double, may be NULL.  groups: 256-thread workgroups launched, 1..2^20.  MASKKV_EINVAL on any violation.

@@ -265,7 +265,7 @@ def maskkv_value_shift(V_now: torch.Tensor, V_prev: torch.Tensor, delta: float, 
 def maskkv_probe(which: int, iters: int, src: Optional[torch.Tensor], dst: torch.Tensor, groups: int,
                  stream=None) -> float:
     """Enqueue a measurement probe (0 matrix pipe, 1 v_exp_f32, 2 streaming copy src -> dst, 3 streaming read of
-    src); returns the work it does (flops, exponentials or bytes moved)."""
+    src, 4 the scoring kernels' instruction mix); returns the work it does (flops, exponentials or bytes moved)."""
     work = ct.c_double(0.0)
     nbytes = src.numel() * src.element_size() if src is not None else 0
     _check(_lib.maskkv_probe(ct.c_int(which), ct.c_int32(iters), _ptr(src) if src is not None else None, _ptr(dst),

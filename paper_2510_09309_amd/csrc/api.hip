@@ -355,21 +355,23 @@ int maskkv_value_shift(const void* V_now, const void* V_prev, int64_t n_tokens, 
 
 int maskkv_probe(int which, int32_t iters, const void* src, void* dst, int64_t bytes, int64_t dst_bytes,
                  int32_t groups, void* stream, double* work) {
-  if (which < 0 || which > 3 || !dst || groups < 1 || groups > (1 << 20)) {
-    set_error("probe: which %d outside 0..3, dst NULL or groups %d outside 1..2^20", which, groups);
+  if (which < 0 || which > 4 || !dst || groups < 1 || groups > (1 << 20)) {
+    set_error("probe: which %d outside 0..4, dst NULL or groups %d outside 1..2^20", which, groups);
     return MASKKV_EINVAL;
   }
   if (which != 2 && dst_bytes < (int64_t)groups * 256 * 4) {
     set_error("probe: dst of %lld bytes is smaller than groups*256 words", (long long)dst_bytes);
     return MASKKV_EINVAL;
   }
-  if (which < 2) {
+  if (which < 2 || which == 4) {
     if (iters < 1) {
       set_error("probe: iters %d < 1", iters);
       return MASKKV_EINVAL;
     }
     // floating-point operations (which = 0: 2*32*32*16 per MFMA, 4 waves x 4 MFMAs per iteration) or exponentials
-    if (work) *work = which == 0 ? (double)groups * 4 * 4 * iters * 32768.0 : (double)groups * 256 * 8 * iters;
+    if (work)
+      *work = which == 1 ? (double)groups * 256 * 8 * iters
+                         : (double)groups * 4 * (which == 0 ? 4 : 16) * iters * 32768.0;
   } else {
     if (!src || bytes < 16 || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15) ||
         (which == 2 && dst_bytes < bytes)) {

@@ -36,7 +36,7 @@ int launch_layer_importance(const void* h_in, const void* h_out, int64_t n, int 
 int launch_value_shift(const void* v_now, const void* v_prev, int64_t n, int width, int dtype, int64_t row_bytes,
                        float delta, float* cos, int32_t* refresh, int32_t* count, hipStream_t stream);
 
-// probe.hip: which = 0 matrix pipe, 1 v_exp_f32, 2 streaming copy, 3 streaming read
+// probe.hip: which = 0 matrix pipe, 1 v_exp_f32, 2 streaming copy, 3 streaming read, 4 scoring instruction mix
 int launch_probe(int which, int iters, const void* src, void* dst, int64_t bytes, int groups, hipStream_t stream);
 
 }  // namespace maskkv

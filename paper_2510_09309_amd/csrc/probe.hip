@@ -32,6 +32,40 @@ __global__ __launch_bounds__(kProbeThreads) void probe_mfma_kernel(int iters, fl
   out[(int64_t)blockIdx.x * kProbeThreads + threadIdx.x] = s;
 }
 
+// The instruction mix of the scoring kernels from registers only: per iteration every wave issues 16 MFMAs (the
+// logits of two 32x32 blocks at head_dim 128) and, per lane, 32 x (fma, v_exp_f32, add) (their exponentials and
+// sums), as independent streams in one basic block.  What this sustains bounds a scoring pass from above: no
+// tile staging, no barriers, no memory.
+__global__ __launch_bounds__(kProbeThreads) void probe_mix_kernel(int iters, float* out) {
+  const uint32_t seed = 0x3C003C00u + (threadIdx.x & 7u);
+  const u32x4 a = {seed, seed + 1u, seed + 2u, seed + 3u};
+  const u32x4 b = {seed + 4u, seed + 5u, seed + 6u, seed + 7u};
+  f32x16 acc[kMfmaChains];
+#pragma unroll
+  for (int u = 0; u < kMfmaChains; ++u) acc[u] = f32x16{};
+  float x[32], sum = 0.f;
+#pragma unroll
+  for (int u = 0; u < 32; ++u) x[u] = 0.01f * (float)(threadIdx.x + u + 1);
+  const float c = 0.127f;
+  for (int i = 0; i < iters; ++i) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int u = 0; u < kMfmaChains; ++u) mfma_step<bf16_t>(a, b, acc[u]);
+#pragma unroll
+    for (int u = 0; u < 32; ++u) {
+      x[u] = fast_exp2(fmaf(x[u], c, -1.0f));
+      sum += x[u];
+    }
+  }
+  float s = sum;
+#pragma unroll
+  for (int u = 0; u < kMfmaChains; ++u)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += acc[u][i];
+  out[(int64_t)blockIdx.x * kProbeThreads + threadIdx.x] = s;
+}
+
 // Every lane runs iters * kExpChains v_exp_f32 (x <- 2^-|x|: the sign and magnitude modifiers are free, the
 // values stay in (0, 1]).
 __global__ __launch_bounds__(kProbeThreads) void probe_exp_kernel(int iters, float* out) {
@@ -94,6 +128,11 @@ int launch_probe(int which, int iters, const void* src, void* dst, int64_t bytes
     hipLaunchKernelGGL(probe_exp_kernel, dim3(groups), dim3(kProbeThreads), 0, stream, iters,
                        reinterpret_cast<float*>(dst));
     return check_launch("probe (exp)");
+  }
+  if (which == 4) {
+    hipLaunchKernelGGL(probe_mix_kernel, dim3(groups), dim3(kProbeThreads), 0, stream, iters,
+                       reinterpret_cast<float*>(dst));
+    return check_launch("probe (mix)");
   }
   if (which == 3) {
     hipLaunchKernelGGL(probe_read_kernel, dim3(groups), dim3(kProbeThreads), 0, stream,

@@ -110,7 +110,8 @@ def test_bad_call_arguments_are_rejected_before_launch(mk):
     probe = lambda which, iters, src, nbytes, dst_bytes, groups: lib.maskkv_probe(
         ct.c_int(which), ct.c_int32(iters), src, f, ct.c_int64(nbytes), ct.c_int64(dst_bytes), ct.c_int32(groups), None,
         None)
-    assert probe(4, 10, None, 0, 1 << 20, 8) == 1              # unknown probe
+    assert probe(5, 10, None, 0, 1 << 20, 8) == 1              # unknown probe
+    assert probe(4, 0, None, 0, 1 << 20, 8) == 1               # no iterations
     assert probe(0, 0, None, 0, 1 << 20, 8) == 1               # no iterations
     assert probe(0, 10, None, 0, 8 * 256 * 4 - 4, 8) == 1      # result buffer too small
     assert probe(2, 0, None, 1024, 1024, 8) == 1               # copy without a source

@@ -77,6 +77,10 @@ def test_measurement_probes_run_and_the_copy_is_exact():
     n_exp = m.maskkv_probe(1, 10, None, out, 8)
     torch.cuda.synchronize()
     assert n_exp == 8 * 256 * 8 * 10 and bool(((out > 0) & (out <= 8)).all())      # eight values in (0, 1] per lane
+    out.fill_(float("nan"))
+    assert m.maskkv_probe(4, 10, None, out, 8) == 8 * 4 * 16 * 10 * 32768.0
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
     src = torch.arange(100003 * 4, dtype=torch.int32, device="cuda")               # a ragged number of 16-byte pieces
     dst = torch.zeros_like(src)
     moved = m.maskkv_probe(2, 0, src, dst, 7)
