@@ -439,6 +439,12 @@ def main():
                                                        layers[i % len(layers)][2], 0.0, Of, None, ws_full, stream),
                        max(4, reps // 4))
 
+    # the same two big calls on one layer's buffers over and over (whatever the caches keep is kept): labelled hot
+    t_score_hot = time_call(lambda i: mk.maskkv_score(desc, layers[0][0], layers[0][1], 0.0, scores, stride, mass,
+                                                      ws_score, stream), reps)
+    t_full_hot = time_call(lambda i: mk.maskkv_attend_full(desc, layers[0][0], layers[0][1], layers[0][2], 0.0, Of,
+                                                           None, ws_full, stream), max(4, reps // 4))
+
     keys_compressed = cap + H * n_m
     flop_attend = 4.0 * n_m * d * keys_compressed
     flop_full = 4.0 * n_m * d * N * H
@@ -458,7 +464,8 @@ def main():
                                f"one layer per step, {len(layers)} resident layers rotated",
                    "global_batch": 1, "seq_len": N},
         "breakdown_ms": {"score": t_score, "select": t_select, "compact": t_compact, "attend": t_attend,
-                         "attend_full": t_full, "score_pass1_in_timed_region": pass1_ms},
+                         "attend_full": t_full, "score_pass1_in_timed_region": pass1_ms,
+                         "score_hot_same_layer": t_score_hot, "attend_full_hot_same_layer": t_full_hot},
         "tokens_scored_evicted_per_s": P / ((t_score + t_select + t_compact) * 1e-3),
         "attend_compressed_tflops": flop_attend / (t_attend * 1e-3) / 1e12,
         "attend_full_tflops": flop_full / (t_full * 1e-3) / 1e12,
