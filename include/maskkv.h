@@ -110,7 +110,8 @@ const char* maskkv_last_error(void);
 
 /*
  * Workspace (DEVICE bytes) needed by maskkv_score for this description.  The workspace
- * holds per-key-segment softmax row statistics between the two passes; contents are
+ * holds per-key-segment softmax row statistics between the two passes and, with more than
+ * 256 voting rows per head, the column sums of every group of 256 rows; contents are
  * scratch.  The size depends on prompt_len: query it with the description the call will
  * use.  256-byte alignment is required.
  */

@@ -11,7 +11,10 @@
 // tiles; a tile never straddles the prompt/response boundary).  All tiles of the launch form one global
 // index space that is divided evenly over a grid of about two workgroups per compute unit, so every
 // workgroup streams the same number of tiles whatever the batch raggedness.  A workgroup walks its range
-// as "segments" (maximal runs inside one region of one head).
+// as "segments" (maximal runs inside one region of one head).  More than 256 voting rows per head (long
+// response spans, grouped-query heads) are cut into groups of 256; every (head, query group) pair has its own
+// copy of the head's tiles in the index space, so a workgroup keeps one set of query fragments for a long run
+// of tiles, and the groups' column sums are added in a fixed order by a last small kernel.
 //
 // Tiling: one workgroup = 4 waves; each wave keeps 64 queries as MFMA operands in registers; K tiles
 // stream through a padded, double-buffered LDS tile shared by the four waves.  Pass 1 puts keys on the
@@ -25,7 +28,7 @@ namespace maskkv {
 
 namespace {
 
-constexpr int kQPerGroup = 256;                        // queries covered per sweep of a segment
+constexpr int kQPerGroup = 256;                        // voting rows per query group
 constexpr int kTargetGroups = 512;                     // about two resident workgroups per compute unit
 constexpr double kSkew = 1.7;                          // tile share of an early workgroup relative to a late one
 constexpr float kLazyLimit = 1.152921504606847e18f;    // 2^60: pass 1 re-centres its reference beyond this
@@ -60,7 +63,8 @@ struct TileMap {
   __host__ __device__ int first_tile(int g) const { return g < G1 ? g * R : G1 * R + (g - G1) * R2; }
   __host__ __device__ int group_of(int tile) const { return tile < G1 * R ? tile / R : G1 + (tile - G1 * R) / R2; }
   int T;                          // tiles in total
-  int toff[MASKKV_MAX_BATCH + 1]; // first global tile of sequence b (all its heads)
+  int nqg;                        // query groups per head: every (head, group) pair owns a copy of the head's tiles
+  int toff[MASKKV_MAX_BATCH + 1]; // first global tile of sequence b (all its heads and query groups)
 };
 
 struct ScoreParams {
@@ -77,6 +81,8 @@ struct ScoreParams {
   float* lse2;        // [B*H][n_query]
   float* scores;      // [B*H][score_stride]
   int64_t score_stride;
+  float* group_sums;  // [B*H][nqg][group_stride] column sums per query group (more than one group only)
+  int64_t group_stride;
   float* prompt_mass; // [B*H] or null
 };
 
@@ -138,10 +144,13 @@ __global__ __launch_bounds__((ScoreCfg<T, D, PASS>::kThreads), (ScoreCfg<T, D, P
     const int nrt = ceil_div(prm.n_resp, C::kTK);
     const int tiles_h = map.with_resp ? npt + nrt : npt;
     const int rem = s - map.toff[b];
-    const int h = rem / tiles_h;
-    const int t_in = rem - h * tiles_h;
+    const int hv = rem / tiles_h;  // (head, query group) pair
+    const int h = hv / map.nqg;
+    const int qgi = hv - h * map.nqg;
+    const int qg = qgi * kQPerGroup;
+    const int t_in = rem - hv * tiles_h;
     const bool prompt = t_in < npt;
-    const int head0 = map.toff[b] + h * tiles_h;
+    const int head0 = map.toff[b] + hv * tiles_h;
     const int region_start = head0 + (prompt ? 0 : npt);
     const int region_end = head0 + (prompt ? npt : tiles_h);
     const int seg_end = min(e, region_end);
@@ -152,7 +161,7 @@ __global__ __launch_bounds__((ScoreCfg<T, D, PASS>::kThreads), (ScoreCfg<T, D, P
     const char* kbase = prm.K.row(b, h, 0);
     const int64_t kstride = prm.K.stride_t;
 
-    for (int qg = 0; qg < prm.n_query; qg += kQPerGroup) {
+    {
       const int q0 = qg + wave * C::kQPerWave;
       if (bh != cur_bh || qg != cur_qg) {
         cur_bh = bh;
@@ -189,14 +198,15 @@ __global__ __launch_bounds__((ScoreCfg<T, D, PASS>::kThreads), (ScoreCfg<T, D, P
         run_l[blk] = 0.f;
       }
 
-      float* out = prm.scores + (int64_t)bh * prm.score_stride;
-      auto flush = [&](int t) {  // tile t of this segment: add the four waves' partials, write scores
+      float* out = map.nqg == 1 ? prm.scores + (int64_t)bh * prm.score_stride
+                                : prm.group_sums + ((int64_t)bh * map.nqg + qgi) * prm.group_stride;
+      auto flush = [&](int t) {  // tile t of this segment: add the waves' partials, write the column sums
         const int j = k0 + t * C::kTK + (int)threadIdx.x;
         if ((int)threadIdx.x < C::kTK && j < k1) {
           float v = 0.f;
 #pragma unroll
           for (int w = 0; w < C::kWaves; ++w) v += cs[t % 3][w][threadIdx.x];
-          out[j] = qg == 0 ? v : out[j] + v;
+          out[j] = v;
         }
       };
 
@@ -334,13 +344,14 @@ __global__ __launch_bounds__(256) void score_merge_kernel(const ScoreParams prm)
   const int P = prm.lens.P[b];
   const int npt = ceil_div(P, map.tk);
   const int nrt = ceil_div(prm.n_resp, map.tk);
-  const int a_p = map.toff[b] + h * (npt + nrt);
-  const int a_r = a_p + npt;
-  const int np_parts = npt > 0 ? map.group_of(a_p + npt - 1) - map.group_of(a_p) + 1 : 0;
-  const int nr_parts = map.group_of(a_r + nrt - 1) - map.group_of(a_r) + 1;
   const int nslot = prm.parts_p + prm.parts_r;
   float mass = 0.f;
   for (int q = threadIdx.x; q < prm.n_query; q += 256) {
+    // the tiles of this row's (head, query group) pair, and the workgroups of pass 1 that touched them
+    const int a_p = map.toff[b] + (h * map.nqg + q / kQPerGroup) * (npt + nrt);
+    const int a_r = a_p + npt;
+    const int np_parts = npt > 0 ? map.group_of(a_p + npt - 1) - map.group_of(a_p) + 1 : 0;
+    const int nr_parts = map.group_of(a_r + nrt - 1) - map.group_of(a_r) + 1;
     const float2* st = prm.stats + (int64_t)bh * nslot * prm.n_query + q;
     // One sweep over the slots, eight independent loads at a time; (M, Lp, Lr) are rescaled on the fly.
     float M = kNegBig, Lp = 0.f, Lr = 0.f;
@@ -378,18 +389,37 @@ __global__ __launch_bounds__(256) void score_merge_kernel(const ScoreParams prm)
   if (threadIdx.x == 0 && prm.prompt_mass) prm.prompt_mass[bh] = red[0];
 }
 
+// More than one query group: scores = sum of the groups' column sums, added in group order.
+__global__ __launch_bounds__(256) void score_group_sum_kernel(const ScoreParams prm, int nqg) {
+  const int bh = blockIdx.y;
+  const int P = prm.lens.P[bh / prm.H];
+  const int j = (int)blockIdx.x * 256 + (int)threadIdx.x;
+  if (j >= P) return;
+  const float* src = prm.group_sums + (int64_t)bh * nqg * prm.group_stride + j;
+  float v = src[0];
+  for (int i = 1; i < nqg; ++i) v += src[(int64_t)i * prm.group_stride];
+  prm.scores[(int64_t)bh * prm.score_stride + j] = v;
+}
+
 int tile_keys(const maskkv_desc*) { return 64; }  // every configuration uses 64-key tiles
+
+int query_groups(const maskkv_desc* d) {
+  return (int)(((int64_t)d->n_query * query_heads_per_kv(d) + kQPerGroup - 1) / kQPerGroup);
+}
+
+int64_t group_stride(const maskkv_desc* d) { return ((int64_t)d->P_max + 63) / 64 * 64; }
 
 TileMap make_map(const maskkv_desc* d, const Lens& lens, bool with_resp) {
   TileMap m;
   m.tk = tile_keys(d);
   m.with_resp = with_resp ? 1 : 0;
+  m.nqg = query_groups(d);
   int t = 0;
   for (int b = 0; b <= MASKKV_MAX_BATCH; ++b) m.toff[b] = 0;
   for (int b = 0; b < d->B; ++b) {
     m.toff[b] = t;
     const int per_head = (lens.P[b] + m.tk - 1) / m.tk + (with_resp ? (d->n_resp + m.tk - 1) / m.tk : 0);
-    t += per_head * d->H;
+    t += per_head * d->H * m.nqg;
   }
   for (int b = d->B; b <= MASKKV_MAX_BATCH; ++b) m.toff[b] = t;
   m.T = t;
@@ -455,6 +485,11 @@ int launch_score_t(ScoreParams& prm, const TileMap& map2, hipStream_t stream, vo
   if (map2.T > 0) {
     prm.map = map2;
     if (int e = launch_pass<T, D, 2>(prm, stream)) return e;
+    if (map2.nqg > 1) {
+      const dim3 grid((unsigned)((prm.group_stride + 255) / 256), prm.B * prm.H);
+      hipLaunchKernelGGL(score_group_sum_kernel, grid, dim3(256), 0, stream, prm, map2.nqg);
+      if (int e = check_launch("score (group sums)")) return e;
+    }
   }
   return mark(events, 3, stream);
 }
@@ -468,8 +503,10 @@ size_t score_workspace_bytes(const maskkv_desc* d, const Lens& lens) {
   const int64_t nq = (int64_t)d->n_query * query_heads_per_kv(d);
   size_t stats = (size_t)(bh * (pp + pr) * nq) * sizeof(float2);
   stats = (stats + 255) / 256 * 256;
-  const size_t lse = (size_t)(bh * nq) * sizeof(float);
-  return stats + (lse + 255) / 256 * 256;
+  const size_t lse = ((size_t)(bh * nq) * sizeof(float) + 255) / 256 * 256;
+  const int nqg = query_groups(d);
+  const size_t sums = nqg > 1 ? (size_t)(bh * nqg * group_stride(d)) * sizeof(float) : 0;
+  return stats + lse + sums;
 }
 
 int launch_score(const maskkv_desc* d, const View& Q, const View& K, const Lens& lens, float scale, float* scores,
@@ -494,6 +531,9 @@ int launch_score(const maskkv_desc* d, const View& Q, const View& K, const Lens&
   stats = (stats + 255) / 256 * 256;
   prm.stats = reinterpret_cast<float2*>(workspace);
   prm.lse2 = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + stats);
+  const size_t lse = ((size_t)(bh * prm.n_query) * sizeof(float) + 255) / 256 * 256;
+  prm.group_sums = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + stats + lse);
+  prm.group_stride = group_stride(d);
   prm.scores = scores;
   prm.score_stride = score_stride;
   prm.prompt_mass = prompt_mass;

@@ -53,7 +53,8 @@ def test_workspace_sizes(mk):
     assert mk.maskkv_attend_workspace_bytes(d, True) > 0
     grouped = mk.Desc(B=1, H=4, d=128, dtype=mk.MASKKV_BF16, n_resp=256, P_max=32768, q_per_kv=7)
     single = mk.Desc(B=1, H=4, d=128, dtype=mk.MASKKV_BF16, n_resp=256, P_max=32768)
-    assert mk.maskkv_score_workspace_bytes(grouped) > 6 * mk.maskkv_score_workspace_bytes(single)   # 7x the voting rows
+    # 7 query groups per head: row statistics of 7x the voting rows plus the groups' column sums (4 B x P each)
+    assert mk.maskkv_score_workspace_bytes(grouped) > mk.maskkv_score_workspace_bytes(single) + 4 * 7 * 32768 * 4
     assert mk.maskkv_select_workspace_bytes(grouped) == mk.maskkv_select_workspace_bytes(single)   # per KV head
     long = mk.Desc(B=2, H=4, d=128, dtype=mk.MASKKV_BF16, n_resp=8, P_max=100000)
     assert mk.maskkv_select_workspace_bytes(long) == 2 * 4 * 25 * 4096 * 8
