@@ -32,7 +32,7 @@ if ROOT not in sys.path:
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
 # measured with rocprofv3 --pmc (profiles/score_pass1_c4_hbm_traffic.md): read + written bytes per launch
-SCORE_PASS1_TRAFFIC_BYTES = {"C4": 141372.1 * 1024 * 2.0 + 1126.0 * 1024}
+SCORE_PASS1_TRAFFIC_BYTES = {"C4": 141373.6 * 1024 * 2.0 + 1126.0 * 1024}
 
 WORKLOADS = {
     # name: (H, d, P, n_m, avg budget, planted, layers resident)
