@@ -80,8 +80,11 @@ __device__ __forceinline__ void vote(int* hist, bool cand, uint32_t bin, int lan
 }
 
 // FINAL = false: chunk stage (grid BH x max_chunks).  FINAL = true: final stage (grid BH); LDS_KEYS says
-// whether its keys are copied to LDS or read in place from the candidate buffer.
-template <bool FINAL, bool LDS_KEYS>
+// whether its keys are copied to LDS or read in place from the candidate buffer.  POOL says where the keys come
+// from: true = pooled scores (chunk stage), false = the chunk stage's candidates (final stage).  Prompts of at
+// most one chunk need no second stage: <FINAL, LDS_KEYS, POOL> = <true, true, true> pools, selects and emits
+// positions in one kernel.
+template <bool FINAL, bool LDS_KEYS, bool POOL>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams prm) {
   extern __shared__ uint32_t lds_keys[];
   __shared__ int hist[kBins];
@@ -127,7 +130,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
   // ---- the keys of this workgroup: n of them, of which the k largest are wanted
   const int c0 = FINAL ? 0 : (int)blockIdx.y * kChunk;  // chunk stage: first prompt position of the chunk
   if (!FINAL && c0 >= P) return;
-  const int n = FINAL ? (nch - 1) * kc + min(kh, P - (nch - 1) * kChunk) : min(kChunk, P - c0);
+  const int n = POOL ? min(kChunk, P - c0) : (nch - 1) * kc + min(kh, P - (nch - 1) * kChunk);
   const int k = FINAL ? kh : min(kh, n);
   // final stage: candidate e of the head sits in chunk min(e / kc, nch-1) of the candidate buffer
   auto cand_slot = [&](int e) -> int64_t {
@@ -153,7 +156,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
       }
     }
   };
-  if (FINAL) {
+  if (!POOL) {
     for (int e = tid; e < n; e += kSelThreads) {
       const uint32_t key = prm.cand_key[cand_slot(e)];
       if (LDS_KEYS) lds_keys[e] = key;
@@ -418,7 +421,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
     if (gt || (eq && eq_rank < need_eq)) {
       const int pos = gt_before + pg + min(eq_rank, need_eq);
       if (FINAL) {
-        if (pos < room) prm.idx[base + pos] = prm.cand_pos[cand_slot(e)];
+        if (pos < room) prm.idx[base + pos] = POOL ? c0 + e : prm.cand_pos[cand_slot(e)];
       } else {
         prm.cand_key[chunk_ws + pos] = kv;
         prm.cand_pos[chunk_ws + pos] = c0 + e;
@@ -501,8 +504,13 @@ int launch_select(const maskkv_desc* d, const Lens& lens, const float* scores, i
   prm.max_chunks = (d->P_max + kChunk - 1) / kChunk;
   prm.cand_key = reinterpret_cast<uint32_t*>(workspace);
   prm.cand_pos = reinterpret_cast<int32_t*>(prm.cand_key + select_cand_slots(d));
+  if (prm.max_chunks == 1) {  // every prompt fits one chunk: pool, select and emit in a single kernel
+    hipLaunchKernelGGL((select_kernel<true, true, true>), dim3(prm.BH), dim3(kSelThreads), kChunk * sizeof(uint32_t),
+                       stream, prm);
+    return check_launch("select (single stage)");
+  }
   if (prm.max_chunks > 0) {
-    hipLaunchKernelGGL((select_kernel<false, true>), dim3(prm.BH, prm.max_chunks), dim3(kSelThreads),
+    hipLaunchKernelGGL((select_kernel<false, true, true>), dim3(prm.BH, prm.max_chunks), dim3(kSelThreads),
                        kChunk * sizeof(uint32_t), stream, prm);
     if (int e = check_launch("select (chunk stage)")) return e;
   }
@@ -511,13 +519,13 @@ int launch_select(const maskkv_desc* d, const Lens& lens, const float* scores, i
     if (dyn > 48 * 1024) {
       static thread_local bool granted = false;  // one-time opt-in to more than the default dynamic LDS size
       if (!granted) {
-        if (int e = raise_lds_limit(&select_kernel<true, true>, kSelLdsCap * sizeof(uint32_t))) return e;
+        if (int e = raise_lds_limit(&select_kernel<true, true, false>, kSelLdsCap * sizeof(uint32_t))) return e;
         granted = true;
       }
     }
-    hipLaunchKernelGGL((select_kernel<true, true>), dim3(prm.BH), dim3(kSelThreads), dyn, stream, prm);
+    hipLaunchKernelGGL((select_kernel<true, true, false>), dim3(prm.BH), dim3(kSelThreads), dyn, stream, prm);
   } else {
-    hipLaunchKernelGGL((select_kernel<true, false>), dim3(prm.BH), dim3(kSelThreads), 0, stream, prm);
+    hipLaunchKernelGGL((select_kernel<true, false, false>), dim3(prm.BH), dim3(kSelThreads), 0, stream, prm);
   }
   return check_launch("select");
 }
