@@ -224,6 +224,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
     wmin[wave] = kmin;
     wmax[wave] = kmax;
   }
+  for (int i = tid; i < kBins; i += kSelThreads) hist[i] = 0;
   __syncthreads();  // also orders the key writes
   if (tid == 0) {
     uint32_t lo = wmin[0], hi = wmax[0];
@@ -248,9 +249,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
       if (lo == hi) break;
       const uint32_t width = hi - lo;
       const int shift = max(0, 32 - __clz(width) - 11);  // (width >> shift) < 2048
-      const int nb = (int)(width >> shift) + 1;
-      for (int i = tid; i < nb; i += kSelThreads) hist[i] = 0;
-      __syncthreads();
+      const int nb = (int)(width >> shift) + 1;  // (the histogram is all zero here: see the bin walk below)
       if (nlist < 0) {
         for (int e0 = 0; e0 < n; e0 += kSelThreads) {
           const int e = e0 + tid;
@@ -272,6 +271,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
         const int b0 = nb - 1 - 2 * tid, b1 = nb - 2 - 2 * tid;
         const int h0 = b0 >= 0 ? hist[b0] : 0;
         const int h1 = b1 >= 0 ? hist[b1] : 0;
+        if (b0 >= 0) hist[b0] = 0;  // every bin is read by exactly one thread, which leaves it clean for the
+        if (b1 >= 0) hist[b1] = 0;  // next round (at least one barrier away)
         int incl = wave_incl_scan(h0 + h1, lane);
         if (lane == 63) wsum[wave][0] = incl;
         __syncthreads();
