@@ -142,6 +142,22 @@ int maskkv_score_profiled(const maskkv_desc* desc, const maskkv_tensor* Q_mask, 
                           float scale, float* scores, int64_t score_stride, float* prompt_mass,
                           void* workspace, size_t workspace_bytes, void* stream, void* const* events);
 
+/*
+ * maskkv_score for callers that cannot allocate device memory or carry a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments and same result as maskkv_score, but the
+ * scratch between the passes lives in an array of MASKKV_STATIC_SCRATCH_BYTES that is part of the library image
+ * (every GPU the library runs on holds its own copy until the process ends).  The call allocates and frees
+ * nothing.  Descriptions whose maskkv_score_workspace_bytes exceed MASKKV_STATIC_SCRATCH_BYTES are rejected with
+ * MASKKV_EWORKSPACE (nothing enqueued).  All calls on one GPU share that GPU's array: two calls that overlap in
+ * time on one GPU (different streams, or different host threads) race; calls on one stream are ordered.  Every
+ * scratch word a call reads is written by the same call first, so nothing needs clearing between calls.  The
+ * first call on a device resolves the array's device address (hipGetSymbolAddress); make that call outside graph
+ * capture.
+ */
+#define MASKKV_STATIC_SCRATCH_BYTES (16u << 20)
+int maskkv_score_static(const maskkv_desc* desc, const maskkv_tensor* Q_mask, const maskkv_tensor* K_full,
+                        float scale, float* scores, int64_t score_stride, float* prompt_mass, void* stream);
+
 /* Workspace (DEVICE bytes) needed by maskkv_select: the candidates that its first stage (one workgroup
  * per 4096 prompt positions) hands to the per-head final stage.  256-byte alignment. */
 int maskkv_select_workspace_bytes(const maskkv_desc* desc, size_t* bytes);

@@ -24,7 +24,7 @@ MAX_BATCH = 64
 
 SYMBOLS = [
     "maskkv_version", "maskkv_strerror", "maskkv_last_error",
-    "maskkv_score_workspace_bytes", "maskkv_score", "maskkv_score_profiled",
+    "maskkv_score_workspace_bytes", "maskkv_score", "maskkv_score_profiled", "maskkv_score_static",
     "maskkv_select_workspace_bytes", "maskkv_select",
     "maskkv_compact",
     "maskkv_attend_workspace_bytes", "maskkv_attend", "maskkv_attend_full",
@@ -163,6 +163,15 @@ def maskkv_score(desc: Desc, Q_mask, K_full, scale: float, scores: torch.Tensor,
     wp, wn = _ws(workspace)
     _check(_lib.maskkv_score(ct.byref(desc.c()), ct.byref(q), ct.byref(k), ct.c_float(scale), _ptr(scores),
                              ct.c_int64(score_stride), _ptr(prompt_mass), wp, wn, _stream(stream)), "maskkv_score")
+
+
+def maskkv_score_static(desc: Desc, Q_mask, K_full, scale: float, scores: torch.Tensor, score_stride: int,
+                        prompt_mass: Optional[torch.Tensor], stream=None) -> None:
+    """maskkv_score with the library's own static scratch array instead of a caller workspace."""
+    q, k = _as_view(Q_mask), _as_view(K_full)
+    _check(_lib.maskkv_score_static(ct.byref(desc.c()), ct.byref(q), ct.byref(k), ct.c_float(scale), _ptr(scores),
+                                    ct.c_int64(score_stride), _ptr(prompt_mass), _stream(stream)),
+           "maskkv_score_static")
 
 
 def maskkv_score_profiled(desc: Desc, Q_mask, K_full, scale: float, scores: torch.Tensor, score_stride: int,

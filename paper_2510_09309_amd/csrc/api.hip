@@ -1,5 +1,6 @@
 // C ABI of the MaskKV library: argument validation and marshalling only; all arithmetic is in the kernels.
 #include <math.h>
+#include <mutex>
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
@@ -124,6 +125,38 @@ int check_workspace(const char* what, void* ws, size_t have, size_t need) {
 
 float pick_scale(const maskkv_desc* d, float scale) { return scale > 0.f ? scale : 1.0f / sqrtf((float)d->d); }
 
+// ---- static scratch of maskkv_score_static: one copy per GPU for the life of the process
+constexpr size_t kStaticScratchBytes = MASKKV_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU (null: not asked for yet)
+
+// Device address of this GPU's copy of `scratch` (the array's name is only a host-side handle: kernels are always
+// given this pointer).  Resolved once per device, with that device current.
+int static_scratch(void** ptr) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    set_error("score_static: hipGetDevice: %s (device %d)", hipGetErrorString(e), dev);
+    (void)hipGetLastError();
+    return MASKKV_EHIP;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      set_error("score_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+      (void)hipGetLastError();
+      return MASKKV_EHIP;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return MASKKV_OK;
+}
+
 }  // namespace
 }  // namespace maskkv
 
@@ -181,6 +214,29 @@ int maskkv_score_profiled(const maskkv_desc* desc, const maskkv_tensor* Q_mask, 
   if (int e = check_workspace("score", workspace, workspace_bytes, score_workspace_bytes(desc, lens))) return e;
   return launch_score(desc, q, k, lens, pick_scale(desc, scale), scores, score_stride, prompt_mass, workspace,
                       reinterpret_cast<hipStream_t>(stream), events);
+}
+
+int maskkv_score_static(const maskkv_desc* desc, const maskkv_tensor* Q_mask, const maskkv_tensor* K_full, float scale,
+                        float* scores, int64_t score_stride, float* prompt_mass, void* stream) {
+  Lens lens;
+  View q, k;
+  if (int e = check_desc(desc, &lens)) return e;
+  if (int e = make_view(desc, Q_mask, "Q_mask", &q)) return e;
+  if (int e = make_view(desc, K_full, "K_full", &k)) return e;
+  if (!scores || score_stride < desc->P_max) {
+    set_error("scores is NULL or score_stride %lld < P_max %d", (long long)score_stride, desc->P_max);
+    return MASKKV_EINVAL;
+  }
+  const size_t need = score_workspace_bytes(desc, lens);
+  if (need > kStaticScratchBytes) {
+    set_error("score_static: this description needs %zu bytes of scratch, the static array holds %zu; use maskkv_score "
+              "with a caller workspace", need, kStaticScratchBytes);
+    return MASKKV_EWORKSPACE;
+  }
+  void* ws = nullptr;
+  if (int e = static_scratch(&ws)) return e;
+  return launch_score(desc, q, k, lens, pick_scale(desc, scale), scores, score_stride, prompt_mass, ws,
+                      reinterpret_cast<hipStream_t>(stream), nullptr);
 }
 
 int maskkv_select_workspace_bytes(const maskkv_desc* desc, size_t* bytes) {
