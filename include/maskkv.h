@@ -158,8 +158,9 @@ int maskkv_score_profiled(const maskkv_desc* desc, const maskkv_tensor* Q_mask, 
 int maskkv_score_static(const maskkv_desc* desc, const maskkv_tensor* Q_mask, const maskkv_tensor* K_full,
                         float scale, float* scores, int64_t score_stride, float* prompt_mass, void* stream);
 
-/* Workspace (DEVICE bytes) needed by maskkv_select: the candidates that its first stage (one workgroup
- * per 4096 prompt positions) hands to the per-head final stage.  256-byte alignment. */
+/* Workspace (DEVICE bytes) needed by maskkv_select: the candidates that the first
+ * stage (one workgroup per 4096 prompt positions) hands to the per-head final stage, and their counts; 0 for
+ * prompts of at most 4096 tokens.  256-byte alignment. */
 int maskkv_select_workspace_bytes(const maskkv_desc* desc, size_t* bytes);
 
 /*
@@ -172,13 +173,18 @@ int maskkv_select_workspace_bytes(const maskkv_desc* desc, size_t* bytes);
  *              written in ascending order to idx[cu_budget[b*H+h] .. cu_budget[b*H+h+1]).
  *   cu_budget = exclusive prefix sum of the clamped budgets, B*H+1 entries.
  * budgets: DEVICE int32 [B*H] (device-resident so that maskkv_head_budgets can feed it
- * without a host round trip).  idx: DEVICE int32 [capacity]; cu_budget: DEVICE int32
- * [B*H+1].  If the clamped budgets sum to more than capacity, rows beyond capacity are not
- * written (and cu_budget still holds the unclipped prefix sums): size capacity as
- * sum of budgets, or B*H*k_l for budgets from maskkv_head_budgets.
+ * without a host round trip).  budgets_host: HOST int32 [B*H] copy of the same values, or
+ * NULL.  With the copy the call checks them before anything is enqueued: a negative budget
+ * is MASKKV_EINVAL, clamped budgets that sum to more than capacity are MASKKV_ECAPACITY.
+ * Without it (budgets that only exist on the device) negative budgets count as 0, and if
+ * the clamped budgets sum to more than capacity the rows beyond capacity are not written
+ * while cu_budget still holds the unclipped prefix sums: size capacity as the sum of the
+ * budgets, or B*H*k_l for budgets from maskkv_head_budgets (their sum never exceeds it).
+ * idx: DEVICE int32 [capacity]; cu_budget: DEVICE int32 [B*H+1].  P_max may not exceed
+ * 4 Mi tokens and B*H*P_max must fit 31 bits (MASKKV_ESHAPE).
  */
 int maskkv_select(const maskkv_desc* desc, const float* scores, int64_t score_stride,
-                  int pool_window, int pool_mode, const int32_t* budgets,
+                  int pool_window, int pool_mode, const int32_t* budgets, const int32_t* budgets_host,
                   int32_t* idx, int32_t* cu_budget, int64_t capacity,
                   void* workspace, size_t workspace_bytes, void* stream);
 

@@ -186,13 +186,19 @@ def maskkv_score_profiled(desc: Desc, Q_mask, K_full, scale: float, scores: torc
            "maskkv_score_profiled")
 
 
+def _host_i32(values: Optional[Sequence[int]]):
+    if values is None:
+        return None
+    return (ct.c_int32 * len(values))(*[int(x) for x in values])
+
+
 def maskkv_select(desc: Desc, scores: torch.Tensor, score_stride: int, pool_window: int, pool_mode: int,
                   budgets: torch.Tensor, idx: torch.Tensor, cu_budget: torch.Tensor, capacity: int,
-                  workspace: Optional[torch.Tensor], stream=None) -> None:
+                  workspace: Optional[torch.Tensor], stream=None, budgets_host: Optional[Sequence[int]] = None) -> None:
     wp, wn = _ws(workspace)
     _check(_lib.maskkv_select(ct.byref(desc.c()), _ptr(scores), ct.c_int64(score_stride), ct.c_int(pool_window),
-                              ct.c_int(pool_mode), _ptr(budgets), _ptr(idx), _ptr(cu_budget), ct.c_int64(capacity),
-                              wp, wn, _stream(stream)), "maskkv_select")
+                              ct.c_int(pool_mode), _ptr(budgets), _host_i32(budgets_host), _ptr(idx), _ptr(cu_budget),
+                              ct.c_int64(capacity), wp, wn, _stream(stream)), "maskkv_select")
 
 
 def maskkv_compact(desc: Desc, K, V, idx: torch.Tensor, cu_budget: torch.Tensor, capacity: int,

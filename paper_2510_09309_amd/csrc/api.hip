@@ -250,11 +250,10 @@ int maskkv_select_workspace_bytes(const maskkv_desc* desc, size_t* bytes) {
   return MASKKV_OK;
 }
 
-int maskkv_select(const maskkv_desc* desc, const float* scores, int64_t score_stride, int pool_window, int pool_mode,
-                  const int32_t* budgets, int32_t* idx, int32_t* cu_budget, int64_t capacity, void* workspace,
-                  size_t workspace_bytes, void* stream) {
-  Lens lens;
-  if (int e = check_desc(desc, &lens)) return e;
+// Validation of maskkv_select: everything the host can know.
+static int check_select(const maskkv_desc* desc, const Lens& lens, const float* scores, int64_t score_stride,
+                        int pool_window, int pool_mode, const int32_t* budgets, const int32_t* budgets_host,
+                        const int32_t* idx, const int32_t* cu_budget, int64_t capacity) {
   if (!scores || !budgets || !cu_budget || score_stride < desc->P_max) {
     set_error("select: scores, budgets or cu_budget NULL, or score_stride %lld < P_max %d", (long long)score_stride,
               desc->P_max);
@@ -272,6 +271,44 @@ int maskkv_select(const maskkv_desc* desc, const float* scores, int64_t score_st
     set_error("select: capacity %lld invalid or idx NULL", (long long)capacity);
     return MASKKV_EINVAL;
   }
+  if (desc->P_max > select_max_prompt()) {
+    set_error("select: prompts above %lld tokens are not supported (P_max = %d)", (long long)select_max_prompt(),
+              desc->P_max);
+    return MASKKV_ESHAPE;
+  }
+  int64_t worst = 0;  // the prefix sums of the clamped budgets are 32-bit
+  for (int b = 0; b < desc->B; ++b) worst += (int64_t)desc->H * lens.P[b];
+  if (worst > 0x7FFFFFFF) {
+    set_error("select: B*H*P = %lld kept rows in the worst case do not fit 32-bit offsets", (long long)worst);
+    return MASKKV_ESHAPE;
+  }
+  if (budgets_host) {
+    int64_t sum = 0;
+    for (int b = 0; b < desc->B; ++b)
+      for (int h = 0; h < desc->H; ++h) {
+        const int32_t k = budgets_host[b * desc->H + h];
+        if (k < 0) {
+          set_error("select: budget %d of (sequence %d, head %d) is negative", k, b, h);
+          return MASKKV_EINVAL;
+        }
+        sum += k < lens.P[b] ? k : lens.P[b];
+      }
+    if (sum > capacity) {
+      set_error("select: the budgets keep %lld rows, capacity is %lld", (long long)sum, (long long)capacity);
+      return MASKKV_ECAPACITY;
+    }
+  }
+  return MASKKV_OK;
+}
+
+int maskkv_select(const maskkv_desc* desc, const float* scores, int64_t score_stride, int pool_window, int pool_mode,
+                  const int32_t* budgets, const int32_t* budgets_host, int32_t* idx, int32_t* cu_budget,
+                  int64_t capacity, void* workspace, size_t workspace_bytes, void* stream) {
+  Lens lens;
+  if (int e = check_desc(desc, &lens)) return e;
+  if (int e = check_select(desc, lens, scores, score_stride, pool_window, pool_mode, budgets, budgets_host, idx,
+                           cu_budget, capacity))
+    return e;
   if (int e = check_workspace("select", workspace, workspace_bytes, select_workspace_bytes(desc))) return e;
   return launch_select(desc, lens, scores, score_stride, pool_window, pool_mode, budgets, idx, cu_budget, capacity,
                        workspace, reinterpret_cast<hipStream_t>(stream));

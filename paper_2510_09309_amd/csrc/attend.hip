@@ -15,8 +15,6 @@ namespace maskkv {
 
 namespace {
 
-constexpr int kAttThreads = 256;  // narrow kernel
-constexpr int kAttWaves = 4;
 // Launches of fewer 128-query tiles than this take the narrow kernel (measured at 256 queries and about 512 keys
 // per head: 32 heads 17 vs 30 us, 64 heads 30 vs 31 us, 96 heads 44 vs 32 us for narrow vs tiled).
 constexpr int kNarrowBelow = 144;
@@ -357,22 +355,24 @@ __global__ __launch_bounds__((AttCfg<T, D>::kThreads)) void attend_kernel(const 
 // XCD, so the head's K/V rows are fetched into one L2 only.
 constexpr int kNarrowVS = 36;  // bf16 elements per transposed-V row: 32 keys + padding
 
-template <int D>
+// NW waves per workgroup split the key axis.
+template <int D, int NW>
 struct NarrowCfg {
+  static constexpr int kThreads = 64 * NW;
   static constexpr int kRowB = D * 2;
   static constexpr int kSteps = kRowB / 32;
   static constexpr int kPPR = kRowB / 16;        // 16-byte pieces per row
   static constexpr int kVP = 32 * kPPR / 64;     // V pieces per lane per block
   static constexpr int kDB = D / 32;
-  static constexpr int kVtBytes = D * kNarrowVS * 2;                       // per wave
-  static constexpr int kMergeBytes = kAttWaves * kDB * 16 * 64 * 4;        // partial O of the four waves
-  static constexpr int kLds = (kMergeBytes > kAttWaves * kVtBytes ? kMergeBytes : kAttWaves * kVtBytes) + kAttWaves * 32 * 8;
+  static constexpr int kVtBytes = D * kNarrowVS * 2;                // per wave
+  static constexpr int kMergeBytes = NW * kDB * 16 * 64 * 4;        // partial O of the waves
+  static constexpr int kLds = (kMergeBytes > NW * kVtBytes ? kMergeBytes : NW * kVtBytes) + NW * 32 * 8;
 };
 
-template <int D>
-__global__ __launch_bounds__(kAttThreads) void attend_narrow_kernel(const AttendParams prm) {
+template <int D, int NW>
+__global__ __launch_bounds__((NarrowCfg<D, NW>::kThreads)) void attend_narrow_kernel(const AttendParams prm) {
   using T = bf16_t;
-  using C = NarrowCfg<D>;
+  using C = NarrowCfg<D, NW>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
   const int nqt = (prm.n_q + 31) / 32;
@@ -395,20 +395,6 @@ __global__ __launch_bounds__(kAttThreads) void attend_narrow_kernel(const Attend
   const int Lk = len_a + prm.n_resp;
   const int nblk = (Lk + 31) / 32;
 
-  const int q = qt * 32 + r;
-  u32x4 qf[C::kSteps];
-  {
-    const char* qrow = prm.Q.group_row(b, h, prm.q_per_kv, prm.n_resp, min(q, prm.n_q - 1));
-#pragma unroll
-    for (int s = 0; s < C::kSteps; ++s) qf[s] = *reinterpret_cast<const u32x4*>(qrow + s * 32 + g * 16);
-  }
-  f32x16 o[C::kDB];
-#pragma unroll
-  for (int db = 0; db < C::kDB; ++db) o[db] = f32x16{};
-  float m = kNegBig, l = 0.f;
-  const float c = prm.c;
-  uint32_t* vt32 = reinterpret_cast<uint32_t*>(smem + wave * C::kVtBytes);
-
   auto key_row = [&](const char* packed, const View& rest, int j) -> const char* {
     return j < len_a ? packed + (int64_t)j * C::kRowB : rest.row(b, h, j - len_a);
   };
@@ -428,8 +414,32 @@ __global__ __launch_bounds__(kAttThreads) void attend_narrow_kernel(const Attend
       vr[2 * i + 1] = *reinterpret_cast<const u32x4*>(key_row(a_v, prm.V2, j1) + col * 16);
     }
   };
+
+  // the first two blocks of this wave are asked for before anything else: their latency covers the query loads
+  u32x4 kfa[C::kSteps], vra[C::kVP], kfb[C::kSteps], vrb[C::kVP];
+  if (wave < nblk) request(wave, kfa, vra);
+  if (wave + NW < nblk) request(wave + NW, kfb, vrb);
+
+  const int q = qt * 32 + r;
+  u32x4 qf[C::kSteps];
+  {
+    const char* qrow = prm.Q.group_row(b, h, prm.q_per_kv, prm.n_resp, min(q, prm.n_q - 1));
+#pragma unroll
+    for (int s = 0; s < C::kSteps; ++s) qf[s] = *reinterpret_cast<const u32x4*>(qrow + s * 32 + g * 16);
+  }
+  f32x16 o[C::kDB];
+#pragma unroll
+  for (int db = 0; db < C::kDB; ++db) o[db] = f32x16{};
+  float m = kNegBig, l = 0.f;
+  const float c = prm.c;
+  uint32_t* vt32 = reinterpret_cast<uint32_t*>(smem + wave * C::kVtBytes);
+
   auto step = [&](int blk, u32x4 (&kf)[C::kSteps], u32x4 (&vr)[C::kVP]) {
-    // V^T of the block into this wave's LDS tile: a 32-bit word holds keys (2*pair, 2*pair+1) of one element
+    // V^T of the block into this wave's LDS tile: a 32-bit word holds keys (2*pair, 2*pair+1) of one element.
+    // The tile is private to the wave; the fences order this block's stores after the previous block's
+    // fragment loads and before this block's.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int i = 0; i < C::kVP / 2; ++i) {
       const int item = lane + i * 64;
@@ -441,11 +451,13 @@ __global__ __launch_bounds__(kAttThreads) void attend_narrow_kernel(const Attend
         vt32[(col * 8 + 2 * w + 1) * (kNarrowVS / 2) + pair] = (a[w] >> 16) | (bq[w] & 0xFFFF0000u);
       }
     }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
     // S^T = K Q^T: keys on rows, queries on columns
     f32x16 s = f32x16{};
 #pragma unroll
     for (int st = 0; st < C::kSteps; ++st) mfma_step<T>(kf[st], qf[st], s);
-    if (blk + 2 * kAttWaves < nblk) request(blk + 2 * kAttWaves, kf, vr);
+    if (blk + 2 * NW < nblk) request(blk + 2 * NW, kf, vr);
     const int nvalid = Lk - blk * 32;
     if (nvalid < 32) {
 #pragma unroll
@@ -494,18 +506,15 @@ __global__ __launch_bounds__(kAttThreads) void attend_narrow_kernel(const Attend
     }
   };
 
-  u32x4 kfa[C::kSteps], vra[C::kVP], kfb[C::kSteps], vrb[C::kVP];
-  if (wave < nblk) request(wave, kfa, vra);
-  if (wave + kAttWaves < nblk) request(wave + kAttWaves, kfb, vrb);
-  for (int blk = wave; blk < nblk; blk += 2 * kAttWaves) {
+  for (int blk = wave; blk < nblk; blk += 2 * NW) {
     step(blk, kfa, vra);
-    if (blk + kAttWaves < nblk) step(blk + kAttWaves, kfb, vrb);
+    if (blk + NW < nblk) step(blk + NW, kfb, vrb);
   }
 
-  // ---- merge the four waves' partial results through LDS (the V tiles are no longer needed)
+  // ---- merge the waves' partial results through LDS (the V tiles are no longer needed)
   const float l_tot = l + xor32(l);
-  float* mo = reinterpret_cast<float*>(smem);                              // [wave][db][i][lane]
-  float2* ml = reinterpret_cast<float2*>(smem + C::kLds - kAttWaves * 32 * 8);  // [wave][query]
+  float* mo = reinterpret_cast<float*>(smem);                          // [wave][db][i][lane]
+  float2* ml = reinterpret_cast<float2*>(smem + C::kLds - NW * 32 * 8);  // [wave][query]
   __syncthreads();
 #pragma unroll
   for (int db = 0; db < C::kDB; ++db)
@@ -515,11 +524,11 @@ __global__ __launch_bounds__(kAttThreads) void attend_narrow_kernel(const Attend
   __syncthreads();
   float M = kNegBig;
 #pragma unroll
-  for (int w = 0; w < kAttWaves; ++w) M = fmaxf(M, ml[w * 32 + r].x);
-  float wgt[kAttWaves];
+  for (int w = 0; w < NW; ++w) M = fmaxf(M, ml[w * 32 + r].x);
+  float wgt[NW];
   float L = 0.f;
 #pragma unroll
-  for (int w = 0; w < kAttWaves; ++w) {
+  for (int w = 0; w < NW; ++w) {
     const float2 v = ml[w * 32 + r];
     wgt[w] = fast_exp2(v.x - M);
     L += wgt[w] * v.y;
@@ -527,22 +536,21 @@ __global__ __launch_bounds__(kAttThreads) void attend_narrow_kernel(const Attend
   if (q >= prm.n_q) return;
   const float inv = 1.f / L;
   char* orow = prm.O.group_row(b, h, prm.q_per_kv, prm.n_resp, q);
-  for (int db = wave; db < C::kDB; db += kAttWaves) {
+  // the kDB * 4 groups of four output elements are dealt over the waves
+  for (int item = wave; item < C::kDB * 4; item += NW) {
+    const int db = item >> 2, qd = item & 3;
+    float v[4];
 #pragma unroll
-    for (int qd = 0; qd < 4; ++qd) {
-      float v[4];
+    for (int e = 0; e < 4; ++e) {
+      float acc = 0.f;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        float acc = 0.f;
-#pragma unroll
-        for (int w = 0; w < kAttWaves; ++w) acc += wgt[w] * mo[((w * C::kDB + db) * 16 + 4 * qd + e) * 64 + lane];
-        v[e] = acc * inv;
-      }
-      u32x2 wout;
-      wout[0] = pack_bf16x2(v[0], v[1]);
-      wout[1] = pack_bf16x2(v[2], v[3]);
-      *reinterpret_cast<u32x2*>(orow + (db * 32 + 8 * qd + 4 * g) * 2) = wout;
+      for (int w = 0; w < NW; ++w) acc += wgt[w] * mo[((w * C::kDB + db) * 16 + 4 * qd + e) * 64 + lane];
+      v[e] = acc * inv;
     }
+    u32x2 wout;
+    wout[0] = pack_bf16x2(v[0], v[1]);
+    wout[1] = pack_bf16x2(v[2], v[3]);
+    *reinterpret_cast<u32x2*>(orow + (db * 32 + 8 * qd + 4 * g) * 2) = wout;
   }
   if (prm.lse && wave == 0 && g == 0) prm.lse[(int64_t)bh * prm.n_q + q] = (M + __log2f(L)) * kLn2;
 }
@@ -650,12 +658,12 @@ bool attend_is_narrow(const maskkv_desc* d, bool full) {
   return qtiles * d->B * d->H < kNarrowBelow;
 }
 
-template <int D>
+template <int D, int NW>
 int launch_attend_narrow(const AttendParams& prm, hipStream_t stream) {
-  using C = NarrowCfg<D>;
+  using C = NarrowCfg<D, NW>;
   static bool raised = false;  // one-time opt-in to more than the default dynamic LDS size
   if (C::kLds > 48 * 1024 && !raised) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_narrow_kernel<D>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_narrow_kernel<D, NW>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, C::kLds);
     if (e != hipSuccess) {
       set_error("attend: cannot raise dynamic LDS limit: %s", hipGetErrorString(e));
@@ -666,7 +674,7 @@ int launch_attend_narrow(const AttendParams& prm, hipStream_t stream) {
   }
   const int nqt = (prm.n_q + 31) / 32;
   const int groups = (prm.BH + 7) / 8 * 8 * nqt;
-  hipLaunchKernelGGL((attend_narrow_kernel<D>), dim3(groups), dim3(kAttThreads), C::kLds, stream, prm);
+  hipLaunchKernelGGL((attend_narrow_kernel<D, NW>), dim3(groups), dim3(C::kThreads), C::kLds, stream, prm);
   return check_launch("attend (narrow)");
 }
 
@@ -748,8 +756,8 @@ int launch_attend(const maskkv_desc* d, const Lens& lens, bool full, const View&
     prm.part_ml = reinterpret_cast<float2*>(reinterpret_cast<char*>(workspace) +
                                             (rows * d->d * sizeof(float) + 255) / 256 * 256);
   }
-  if (attend_is_narrow(d, full))
-    return d->d == 128 ? launch_attend_narrow<128>(prm, stream) : launch_attend_narrow<64>(prm, stream);
+  if (attend_is_narrow(d, full))  // (eight waves per 32-query tile measured slower: 20.6 vs 17.6 us at the 32k prompt)
+    return d->d == 128 ? launch_attend_narrow<128, 4>(prm, stream) : launch_attend_narrow<64, 4>(prm, stream);
   if (d->dtype == MASKKV_BF16)
     return d->d == 128 ? launch_attend_t<bf16_t, 128>(prm, d->B, stream) : launch_attend_t<bf16_t, 64>(prm, d->B, stream);
   return d->d == 128 ? launch_attend_t<float, 128>(prm, d->B, stream) : launch_attend_t<float, 64>(prm, d->B, stream);

@@ -13,6 +13,7 @@ int launch_score(const maskkv_desc* d, const View& Q, const View& K, const Lens&
 
 // select.hip
 size_t select_workspace_bytes(const maskkv_desc* d);
+int64_t select_max_prompt();
 int launch_select(const maskkv_desc* d, const Lens& lens, const float* scores, int64_t score_stride, int window,
                   int mode, const int32_t* budgets, int32_t* idx, int32_t* cu_budget, int64_t capacity,
                   void* workspace, hipStream_t stream);

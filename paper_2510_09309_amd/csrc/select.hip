@@ -1,27 +1,23 @@
-// Score smoothing + per-head top-k (MaskKV Section 3.3: S_keep = argtopk(I, k_{l,h})), and the
-// head-level budget formula of Stage 2.
+// Score smoothing + per-head top-k (MaskKV Section 3.3: S_keep = argtopk(I, k_{l,h})), and the head-level
+// budget formula of Stage 2.
 //
 // Two stages, because one workgroup per head would leave most of the chip idle:
 //   chunk stage  one workgroup per 4096 prompt positions of a head: pools the scores, turns them into
-//                order-preserving 32-bit keys, finds the chunk's own top-min(k, chunk) under the same order
-//                (larger key first, ties to the lower position) and writes them, in ascending position
-//                order, as (key, position) candidates.  Every member of the head's top-k is in its chunk's
-//                top-k, so the candidates of all chunks are a superset of the answer, already sorted by
-//                position.
-//   final stage  one workgroup per head: the same selection over the candidates, emitting positions.
+//                order-preserving 32-bit keys and writes, in ascending position order, every (key, position)
+//                whose key is at least t0, the k-th largest key of the chunk (k = the head's budget).  The
+//                head's k-th largest key tau is never below a chunk's k-th largest key (fewer than k keys of
+//                the whole head are above tau), so every key >= tau of every chunk - all members of the
+//                answer and all their ties - is among the candidates.
+//   final stage  one workgroup per head: exact selection over the candidates (larger key first, ties to the
+//                lower position), positions emitted in ascending order.
+// Prompts of at most one chunk skip the chunk stage: the final stage pools the scores itself.
 //
-// Selection inside a workgroup (16 waves, keys in LDS): the k-th largest key tau is found by range
-// refinement: the current key range [lo, hi] is cut into at most 2048 equal bins, an LDS histogram locates
-// the bin that holds the k-th largest key, and that bin becomes the new range (three rounds always reach a
-// single key).  Scanning everything with LDS atomics is slow when almost every key falls into the same few
-// bins (a flat background under a few large scores), so the refinement normally runs on a short candidate
-// list: every thread remembers the largest keys among those it handled; the k-th largest of those 1024*c
-// remembered keys (c = ceil(k/1024)), or the lower edge of the histogram bin that holds it, is a lower bound
-// t0 of tau, because they are a subset of the keys;
-// the keys >= t0 - typically little more than k of them - are the candidates.  Inputs with k > 4096, or
-// whose candidates do not fit the list, take the whole-array path.
-// The kept set is "key > tau" plus the first (k - count_gt) entries with key == tau, emitted in
-// ascending order with ballot/popcount prefix sums, each wave walking one contiguous slice.
+// Selection inside a workgroup (both stages): range refinement.  The key range [lo, hi] is cut into at most 2048 equal bins,
+// an LDS histogram (votes of a wave for one bin are merged into one atomic) locates the bin that holds the
+// k-th largest key, and that bin becomes the range: at most three rounds reach a single key tau.  One wave
+// walks the bins (32 consecutive bins per lane, a wave scan, then the owning lane's own 32), so a round is
+// two barriers.  The kept set is "key > tau" plus the first (k - count_gt) entries with key == tau, written
+// in order with ballot/popcount prefix sums, each wave walking one contiguous slice.
 #include "kernels.hpp"
 
 namespace maskkv {
@@ -31,10 +27,11 @@ namespace {
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kChunk = 4096;       // prompt positions per chunk-stage workgroup
-constexpr int kSelLdsCap = 32768;  // final stage: keys kept in LDS (128 KB) next to the histogram and the list
+constexpr int kSelLdsCap = 32768;  // final stage: keys kept in LDS (128 KB) next to the histogram
 constexpr int kBins = 2048;
-constexpr int kListCap = 4096;
-constexpr int kTopC = 4;           // largest keys remembered per thread
+constexpr int kBinsPerLane = kBins / 64;
+constexpr int kHistWords = kBins + kBins / kBinsPerLane;  // one pad word per 32 bins: conflict-free lane walks
+constexpr int kMaxChunks = 1024;   // chunk offsets of a head are kept in LDS: prompts of up to 4 Mi tokens
 
 struct SelectParams {
   Lens lens;
@@ -46,8 +43,15 @@ struct SelectParams {
   int32_t* idx;
   int32_t* cu;
   int64_t capacity;
+  int lds_words;       // final stage: keys that fit its dynamic LDS
   uint32_t* cand_key;  // [BH][max_chunks][kChunk] candidates of the chunk stage
   int32_t* cand_pos;   // [BH][max_chunks][kChunk]
+  int32_t* cand_cnt;   // [BH][max_chunks] candidates per chunk
+};
+
+struct SelState {
+  uint32_t lo, hi;  // current key range
+  int krem;         // rank wanted inside it
 };
 
 __device__ __forceinline__ uint32_t order_key(float v) {
@@ -56,334 +60,365 @@ __device__ __forceinline__ uint32_t order_key(float v) {
   return u ^ ((u >> 31) ? 0xFFFFFFFFu : 0x80000000u);  // larger float <=> larger unsigned key
 }
 
-__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int n = __shfl_up(v, o, 64);
-    if (lane >= o) v += n;
-  }
+// Wave-level scans and reductions on the data-parallel-primitive path of the vector ALU (row shifts inside the
+// rows of 16 lanes, then the two row broadcasts): six dependent vector instructions, no LDS round trips.
+template <typename Op>
+__device__ __forceinline__ int wave_scan(int v, int identity, Op op) {
+  v = op(v, __builtin_amdgcn_update_dpp(identity, v, 0x111, 0xf, 0xf, false));  // row_shr:1
+  v = op(v, __builtin_amdgcn_update_dpp(identity, v, 0x112, 0xf, 0xf, false));  // row_shr:2
+  v = op(v, __builtin_amdgcn_update_dpp(identity, v, 0x114, 0xf, 0xf, false));  // row_shr:4
+  v = op(v, __builtin_amdgcn_update_dpp(identity, v, 0x118, 0xf, 0xf, false));  // row_shr:8
+  v = op(v, __builtin_amdgcn_update_dpp(identity, v, 0x142, 0xa, 0xf, false));  // row_bcast:15 into rows 1, 3
+  v = op(v, __builtin_amdgcn_update_dpp(identity, v, 0x143, 0xc, 0xf, false));  // row_bcast:31 into rows 2, 3
   return v;
 }
 
-// One histogram vote; lanes of a wave that all vote for the same bin are merged into one atomic.
-__device__ __forceinline__ void vote(int* hist, bool cand, uint32_t bin, int lane) {
-  const uint64_t cmask = __ballot(cand);
-  if (!cmask) return;
-  const int leader = __ffsll((unsigned long long)cmask) - 1;
-  const uint32_t b0 = __shfl(bin, leader, 64);
-  const uint64_t same = __ballot(cand && bin == b0);
-  if (same == cmask) {
-    if (lane == leader) atomicAdd(&hist[b0], __popcll(cmask));
-  } else if (cand) {
-    atomicAdd(&hist[bin], 1);
+__device__ __forceinline__ int wave_incl_scan(int v, int) {
+  return wave_scan(v, 0, [](int a, int b) { return a + b; });
+}
+
+// Bins are numbered from the top of the range (bin 0 holds the largest keys) and padded by one word per 32.
+__device__ __forceinline__ int hist_slot(int top_bin) { return top_bin + top_bin / kBinsPerLane; }
+
+// One histogram vote per lane; the lanes of a wave that vote for the bin of the first (then second) voting
+// lane are merged into one atomic each, the rest vote on their own.  Called by all 64 lanes.
+__device__ __forceinline__ void vote(int* hist, bool cand, int top_bin, int lane) {
+  uint64_t cmask = __ballot(cand);
+#pragma unroll
+  for (int it = 0; it < 2; ++it) {
+    if (!cmask) return;
+    const int leader = __ffsll((unsigned long long)cmask) - 1;
+    const int b0 = __builtin_amdgcn_readlane(top_bin, leader);
+    const bool mine = cand && top_bin == b0;
+    const uint64_t same = __ballot(mine);
+    if (lane == leader) atomicAdd(&hist[hist_slot(b0)], __popcll(same));
+    if (mine) cand = false;
+    cmask &= ~same;
+  }
+  if (cand) atomicAdd(&hist[hist_slot(top_bin)], 1);
+}
+
+// Geometry of one refinement round over the key range [lo, hi].
+struct Round {
+  uint32_t lo;
+  int shift, nb;
+  __device__ __forceinline__ Round(uint32_t lo_, uint32_t hi_) : lo(lo_) {
+    const uint32_t width = hi_ - lo_;
+    shift = max(0, 32 - __clz(width) - 11);  // (width >> shift) < 2048
+    nb = (int)(width >> shift) + 1;
+  }
+  __device__ __forceinline__ int top_bin(uint32_t key) const { return nb - 1 - (int)((key - lo) >> shift); }
+};
+
+// One wave, after all votes of a round: find the bin (from the top) that holds the krem-th largest key, make it
+// the new range, and leave the histogram zeroed for the next round.
+__device__ __forceinline__ void pick_bin(int* hist, const Round& rd, uint32_t hi, int krem, int lane, SelState* st) {
+  int h[kBinsPerLane];
+  int s = 0;
+  int* mine = hist + lane * (kBinsPerLane + 1);
+#pragma unroll
+  for (int j = 0; j < kBinsPerLane; ++j) {
+    h[j] = mine[j];
+    mine[j] = 0;
+    s += h[j];
+  }
+  const int incl = wave_incl_scan(s, lane);
+  int above = incl - s;
+  if (incl >= krem && above < krem) {  // exactly one lane owns the bin
+    int bsel = -1;
+#pragma unroll
+    for (int j = 0; j < kBinsPerLane; ++j) {
+      if (bsel < 0) {
+        if (above + h[j] >= krem)
+          bsel = lane * kBinsPerLane + j;
+        else
+          above += h[j];
+      }
+    }
+    const uint32_t nlo = rd.lo + ((uint32_t)(rd.nb - 1 - bsel) << rd.shift);
+    const uint32_t span = rd.shift == 0 ? 0u : ((1u << rd.shift) - 1u);
+    st->lo = nlo;
+    st->hi = (uint32_t)min((uint64_t)hi, (uint64_t)nlo + span);
+    st->krem = krem - above;
   }
 }
 
-// FINAL = false: chunk stage (grid BH x max_chunks).  FINAL = true: final stage (grid BH); LDS_KEYS says
-// whether its keys are copied to LDS or read in place from the candidate buffer.  POOL says where the keys come
-// from: true = pooled scores (chunk stage), false = the chunk stage's candidates (final stage).  Prompts of at
-// most one chunk need no second stage: <FINAL, LDS_KEYS, POOL> = <true, true, true> pools, selects and emits
-// positions in one kernel.
-template <bool FINAL, bool LDS_KEYS, bool POOL>
-__global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams prm) {
-  extern __shared__ uint32_t lds_keys[];
-  __shared__ int hist[kBins];
-  __shared__ uint32_t list[kListCap];
-  __shared__ int wsum[kSelWaves][2];
+// Pooled score of position j of a head (mean: in-range terms added from the lowest index upwards in fp32, one
+// division by their count; max: the maximum), as an order-preserving key.
+__device__ __forceinline__ uint32_t pooled_key(const float* x, int j, int P, int r, int mode) {
+  const int lo = max(0, j - r);
+  const int hi = min(P - 1, j + r);
+  float v = x[lo];
+  if (mode == MASKKV_POOL_MAX) {
+    for (int t = lo + 1; t <= hi; ++t) v = fmaxf(v, x[t]);
+  } else {
+    for (int t = lo + 1; t <= hi; ++t) v = __fadd_rn(v, x[t]);
+    v = __fdiv_rn(v, (float)(hi - lo + 1));
+  }
+  return order_key(v);
+}
+
+// Keys of the four consecutive positions j0 .. j0+3 (0 for positions past the prompt: below every real key).
+__device__ __forceinline__ void pooled_keys4(const float* x, int j0, int P, int r, int mode, uint32_t (&key)[4]) {
+  if (r <= 3 && mode == MASKKV_POOL_MEAN) {
+    // ten loads serve four windows of up to seven terms
+    float v[10];
+#pragma unroll
+    for (int i = 0; i < 10; ++i) {
+      const int j = j0 - 3 + i;
+      v[i] = (j >= 0 && j < P) ? x[j] : 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int j = j0 + e;
+      key[e] = 0u;
+      if (j < P) {
+        const int lo = max(0, j - r), hi = min(P - 1, j + r);
+        float acc = 0.f;
+        bool first = true;
+#pragma unroll
+        for (int t = -3; t <= 3; ++t) {
+          const int jj = j + t;
+          if (jj >= lo && jj <= hi) {  // in-range terms only, lowest index first
+            acc = first ? v[e + 3 + t] : __fadd_rn(acc, v[e + 3 + t]);
+            first = false;
+          }
+        }
+        key[e] = order_key(__fdiv_rn(acc, (float)(hi - lo + 1)));
+      }
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) key[e] = j0 + e < P ? pooled_key(x, j0 + e, P, r, mode) : 0u;
+  }
+}
+
+__device__ __forceinline__ uint32_t wave_min(uint32_t v) {
+  const int r = wave_scan((int)v, -1, [](int a, int b) { return (int)min((uint32_t)a, (uint32_t)b); });
+  return (uint32_t)__builtin_amdgcn_readlane(r, 63);
+}
+__device__ __forceinline__ uint32_t wave_max(uint32_t v) {
+  const int r = wave_scan((int)v, 0, [](int a, int b) { return (int)max((uint32_t)a, (uint32_t)b); });
+  return (uint32_t)__builtin_amdgcn_readlane(r, 63);
+}
+
+// ---- chunk stage: grid (BH, max_chunks)
+__global__ __launch_bounds__(kSelThreads) void select_chunk_kernel(const SelectParams prm) {
+  __shared__ int hist[kHistWords];
   __shared__ uint32_t wmin[kSelWaves], wmax[kSelWaves];
-  __shared__ uint32_t sh_lo, sh_hi;
-  __shared__ int sh_krem, sh_base, sh_nlist, sh_bincount;
+  __shared__ int wsum[kSelWaves];
+  __shared__ SelState st;
 
   const int bh = blockIdx.x;
   const int b = bh / prm.H;
   const int P = prm.lens.P[b];
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int kh = min(max(prm.budgets[bh], 0), P);  // the head's budget
-  const int nch = (P + kChunk - 1) / kChunk;
-  const int kc = min(kh, kChunk);                  // candidates that every full chunk delivers
-  const int64_t head_ws = (int64_t)bh * prm.max_chunks * kChunk;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kh = min(max(prm.budgets[bh], 0), P);
+  const int c0 = (int)blockIdx.y * kChunk;
+  if (c0 >= P || kh == 0) return;  // the final stage reads neither this chunk's count nor anything of a head without budget
+  const int n = min(kChunk, P - c0);
+  const int kc = min(kh, n);
 
-  int base = 0;
-  if (FINAL) {
-    // ---- offset of this head's slice: exclusive prefix sum of the clamped budgets
-    int part = 0;
-    for (int i = tid; i < bh; i += kSelThreads) part += min(max(prm.budgets[i], 0), prm.lens.P[i / prm.H]);
-    part = wave_incl_scan(part, lane);
-    if (lane == 63) wsum[wave][0] = part;
-    __syncthreads();
-    if (tid == 0) {
-      int s = 0;
-      for (int w = 0; w < kSelWaves; ++w) s += wsum[w][0];
-      sh_base = s;
-    }
-    __syncthreads();
-    base = sh_base;
-    if (tid == 0) {
-      prm.cu[bh] = base;
-      if (bh == prm.BH - 1) prm.cu[prm.BH] = base + kh;
-    }
-  }
-  if (kh == 0) return;
-
-  // ---- the keys of this workgroup: n of them, of which the k largest are wanted
-  const int c0 = FINAL ? 0 : (int)blockIdx.y * kChunk;  // chunk stage: first prompt position of the chunk
-  if (!FINAL && c0 >= P) return;
-  const int n = POOL ? min(kChunk, P - c0) : (nch - 1) * kc + min(kh, P - (nch - 1) * kChunk);
-  const int k = FINAL ? kh : min(kh, n);
-  // final stage: candidate e of the head sits in chunk min(e / kc, nch-1) of the candidate buffer
-  auto cand_slot = [&](int e) -> int64_t {
-    const int ch = min(e / kc, nch - 1);
-    return head_ws + (int64_t)ch * kChunk + (e - ch * kc);
-  };
-  auto key_at = [&](int e) -> uint32_t {
-    return (FINAL && !LDS_KEYS) ? prm.cand_key[cand_slot(e)] : lds_keys[e];
-  };
-
+  for (int i = tid; i < kHistWords; i += kSelThreads) hist[i] = 0;
+  uint32_t key[4];
+  pooled_keys4(prm.scores + (int64_t)bh * prm.score_stride, c0 + 4 * tid, P, (prm.window - 1) / 2, prm.mode, key);
+  const int nmine = min(max(n - 4 * tid, 0), 4);  // this thread's real keys: key[0 .. nmine)
   uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
-  uint32_t top[kTopC] = {0u, 0u, 0u, 0u};  // this thread's largest keys, descending (0 = none: below every real key)
-  auto remember = [&](uint32_t key) {
-    kmin = min(kmin, key);
-    kmax = max(kmax, key);
-    if (key > top[kTopC - 1]) {
-      top[kTopC - 1] = key;
 #pragma unroll
-      for (int i = kTopC - 1; i > 0; --i) {
-        const uint32_t a = top[i - 1], bq = top[i];
-        top[i - 1] = max(a, bq);
-        top[i] = min(a, bq);
-      }
+  for (int e = 0; e < 4; ++e)
+    if (e < nmine) {
+      kmin = min(kmin, key[e]);
+      kmax = max(kmax, key[e]);
     }
-  };
-  if (!POOL) {
-    for (int e = tid; e < n; e += kSelThreads) {
-      const uint32_t key = prm.cand_key[cand_slot(e)];
-      if (LDS_KEYS) lds_keys[e] = key;
-      remember(key);
-    }
-  } else {
-    // pooled scores -> order-preserving keys
-    const float* x = prm.scores + (int64_t)bh * prm.score_stride;
-    const int r = (prm.window - 1) / 2;
-    if (r <= 3 && prm.mode == MASKKV_POOL_MEAN) {
-      // four consecutive positions per thread: ten loads serve four windows of up to seven terms
-      for (int e0 = tid * 4; e0 < n; e0 += kSelThreads * 4) {
-        const int j0 = c0 + e0;
-        float v[10];
-#pragma unroll
-        for (int i = 0; i < 10; ++i) {
-          const int j = j0 - 3 + i;
-          v[i] = (j >= 0 && j < P) ? x[j] : 0.f;
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int j = j0 + e;
-          if (j < P) {
-            const int lo = max(0, j - r), hi = min(P - 1, j + r);
-            float acc = 0.f;
-            bool first = true;
-#pragma unroll
-            for (int t = -3; t <= 3; ++t) {
-              const int jj = j + t;
-              if (jj >= lo && jj <= hi) {  // in-range terms only, lowest index first
-                acc = first ? v[e + 3 + t] : __fadd_rn(acc, v[e + 3 + t]);
-                first = false;
-              }
-            }
-            const uint32_t key = order_key(__fdiv_rn(acc, (float)(hi - lo + 1)));
-            lds_keys[e0 + e] = key;
-            remember(key);
-          }
-        }
-      }
-    } else {
-      for (int e = tid; e < n; e += kSelThreads) {
-        const int j = c0 + e;
-        const int lo = max(0, j - r);
-        const int hi = min(P - 1, j + r);
-        float v = x[lo];
-        if (prm.mode == MASKKV_POOL_MAX) {
-          for (int t = lo + 1; t <= hi; ++t) v = fmaxf(v, x[t]);
-        } else {
-          for (int t = lo + 1; t <= hi; ++t) v = __fadd_rn(v, x[t]);
-          v = __fdiv_rn(v, (float)(hi - lo + 1));
-        }
-        const uint32_t key = order_key(v);
-        lds_keys[e] = key;
-        remember(key);
-      }
-    }
-  }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, 64));
-    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, 64));
-  }
+  kmin = wave_min(kmin);
+  kmax = wave_max(kmax);
   if (lane == 0) {
     wmin[wave] = kmin;
     wmax[wave] = kmax;
   }
-  for (int i = tid; i < kBins; i += kSelThreads) hist[i] = 0;
-  __syncthreads();  // also orders the key writes
-  if (tid == 0) {
-    uint32_t lo = wmin[0], hi = wmax[0];
-    for (int w = 1; w < kSelWaves; ++w) {
-      lo = min(lo, wmin[w]);
-      hi = max(hi, wmax[w]);
-    }
-    sh_lo = lo;
-    sh_hi = hi;
-    sh_krem = k;
-    sh_nlist = -1;  // no candidate list yet: rounds scan all n keys
-  }
   __syncthreads();
-
-  // ---- range refinement until a single key remains.  State in LDS: the key range [sh_lo, sh_hi], the rank
-  // sh_krem wanted inside it, and sh_nlist (>= 0: scan list[0..sh_nlist), < 0: scan all n keys).
-  auto refine = [&](int max_rounds) {
-    for (int round = 0; round < max_rounds; ++round) {
-      const uint32_t lo = sh_lo, hi = sh_hi;
-      const int krem = sh_krem;
-      const int nlist = sh_nlist;
-      if (lo == hi) break;
-      const uint32_t width = hi - lo;
-      const int shift = max(0, 32 - __clz(width) - 11);  // (width >> shift) < 2048
-      const int nb = (int)(width >> shift) + 1;  // (the histogram is all zero here: see the bin walk below)
-      if (nlist < 0) {
-        for (int e0 = 0; e0 < n; e0 += kSelThreads) {
-          const int e = e0 + tid;
-          const uint32_t key = e < n ? key_at(e) : 0u;
-          const bool cand = e < n && key >= lo && key <= hi;
-          vote(hist, cand, cand ? ((key - lo) >> shift) : 0u, lane);
-        }
-      } else {
-        for (int e0 = 0; e0 < nlist; e0 += kSelThreads) {
-          const int e = e0 + tid;
-          const uint32_t key = e < nlist ? list[e] : 0u;
-          const bool cand = e < nlist && key >= lo && key <= hi;
-          vote(hist, cand, cand ? ((key - lo) >> shift) : 0u, lane);
-        }
+  uint32_t lo = wmin[0], hi = wmax[0];
+#pragma unroll
+  for (int w = 1; w < kSelWaves; ++w) {
+    lo = min(lo, wmin[w]);
+    hi = max(hi, wmax[w]);
+  }
+  // ---- the chunk's kc-th largest key, exactly: range refinement over the keys in registers
+  if (kc < n) {
+    int krem = kc;
+    for (int round = 0; round < 4 && lo != hi; ++round) {
+      const Round rd(lo, hi);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool cand = e < nmine && key[e] >= lo && key[e] <= hi;
+        vote(hist, cand, cand ? rd.top_bin(key[e]) : 0, lane);
       }
       __syncthreads();
-      // Walk the bins from the top, two per thread; exactly one bin straddles the krem-th largest key.
-      {
-        const int b0 = nb - 1 - 2 * tid, b1 = nb - 2 - 2 * tid;
-        const int h0 = b0 >= 0 ? hist[b0] : 0;
-        const int h1 = b1 >= 0 ? hist[b1] : 0;
-        if (b0 >= 0) hist[b0] = 0;  // every bin is read by exactly one thread, which leaves it clean for the
-        if (b1 >= 0) hist[b1] = 0;  // next round (at least one barrier away)
-        int incl = wave_incl_scan(h0 + h1, lane);
-        if (lane == 63) wsum[wave][0] = incl;
-        __syncthreads();
-        for (int w = 0; w < wave; ++w) incl += wsum[w][0];
-        const int before = incl - (h0 + h1);
-        if (incl >= krem && before < krem) {
-          const bool in0 = before + h0 >= krem;
-          const int bsel = in0 ? b0 : b1;
-          const int above = in0 ? before : before + h0;
-          const uint32_t nlo = lo + ((uint32_t)bsel << shift);
-          const uint32_t span = (shift == 0) ? 0u : ((1u << shift) - 1u);
-          sh_lo = nlo;
-          sh_hi = (uint32_t)min((uint64_t)hi, (uint64_t)nlo + span);
-          sh_krem = krem - above;
-          sh_bincount = in0 ? h0 : h1;
-        }
-        __syncthreads();
-      }
-      // A bin with a single key: that key is the answer, fetch it instead of refining the bin further.
-      if (sh_bincount == 1 && sh_lo != sh_hi) {
-        const uint32_t nlo = sh_lo, nhi = sh_hi;
-        __syncthreads();
-        const int cnt = nlist < 0 ? n : nlist;
-        for (int e = tid; e < cnt; e += kSelThreads) {
-          const uint32_t key = nlist < 0 ? key_at(e) : list[e];
-          if (key >= nlo && key <= nhi) {
-            sh_lo = key;
-            sh_hi = key;
-          }
-        }
-        __syncthreads();
-      }
-      // First whole-array round: move the chosen bin's keys to the short list if they fit.
-      if (nlist < 0 && sh_lo != sh_hi && sh_bincount <= kListCap) {
-        const uint32_t nlo = sh_lo, nhi = sh_hi;
-        if (tid == 0) sh_nlist = 0;
-        __syncthreads();
-        for (int e0 = 0; e0 < n; e0 += kSelThreads) {
-          const int e = e0 + tid;
-          const uint32_t key = e < n ? key_at(e) : 0u;
-          const bool cand = e < n && key >= nlo && key <= nhi;
-          const uint64_t m = __ballot(cand);
-          if (m) {
-            int pos = 0;
-            if (lane == __ffsll((unsigned long long)m) - 1) pos = atomicAdd(&sh_nlist, __popcll(m));
-            pos = __shfl(pos, __ffsll((unsigned long long)m) - 1, 64);
-            if (cand) list[pos + __popcll(m & ((1ull << lane) - 1ull))] = key;
-          }
-        }
-        __syncthreads();
-      }
+      if (wave == 0) pick_bin(hist, rd, hi, krem, lane, &st);
+      __syncthreads();
+      lo = st.lo;
+      hi = st.hi;
+      krem = st.krem;
     }
-  };
+  }
+  const uint32_t t0 = lo;  // kc >= n: the smallest key, everything is a candidate
 
-  const uint32_t all_lo = sh_lo, all_hi = sh_hi;
-  const int c = (k + kSelThreads - 1) / kSelThreads;  // remembered keys per thread that the bound needs
-  bool short_list = c <= kTopC;
-  if (short_list) {
-    // t0 = k-th largest of the remembered keys
-    uint32_t tmin = 0xFFFFFFFFu;
+  // ---- every key >= t0, in position order
+  int mine = 0;
 #pragma unroll
-    for (int i = 0; i < kTopC; ++i)
-      if (i < c) {
-        list[tid * c + i] = top[i];
-        tmin = min(tmin, top[i]);
+  for (int e = 0; e < 4; ++e) mine += (e < nmine && key[e] >= t0) ? 1 : 0;
+  const int incl = wave_incl_scan(mine, lane);
+  if (lane == 63) wsum[wave] = incl;
+  __syncthreads();
+  int before = incl - mine;
+  int total = 0;
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) {
+    const int v = wsum[w];
+    if (w < wave) before += v;
+    total += v;
+  }
+  const int64_t ws = ((int64_t)bh * prm.max_chunks + blockIdx.y) * kChunk;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    if (e < nmine && key[e] >= t0) {
+      prm.cand_key[ws + before] = key[e];
+      prm.cand_pos[ws + before] = c0 + 4 * tid + e;
+      ++before;
+    }
+  }
+  if (tid == 0) prm.cand_cnt[(int64_t)bh * prm.max_chunks + blockIdx.y] = total;
+}
+
+// ---- final stage: grid (BH).  POOL: the keys are the pooled scores of a prompt of at most one chunk;
+// otherwise they are the chunk stage's candidates.
+template <bool POOL>
+__global__ __launch_bounds__(kSelThreads) void select_final_kernel(const SelectParams prm) {
+  extern __shared__ uint32_t lds_keys[];
+  __shared__ int hist[kHistWords];
+  __shared__ int coff[kMaxChunks + 1];  // candidates before chunk c
+  __shared__ int wsum[kSelWaves][2];
+  __shared__ uint32_t wmin[kSelWaves], wmax[kSelWaves];
+  __shared__ SelState st;
+
+  const int bh = blockIdx.x;
+  const int b = bh / prm.H;
+  const int h = bh - b * prm.H;
+  const int P = prm.lens.P[b];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kh = min(max(prm.budgets[bh], 0), P);
+  const int nch = POOL ? 1 : (P + kChunk - 1) / kChunk;  // (POOL: the prompt is one flat list)
+  const int64_t head_ws = (int64_t)bh * prm.max_chunks * kChunk;
+
+  // ---- offset of this head's slice (exclusive prefix sum of the clamped budgets) and of every chunk's
+  // candidates (inclusive scan of the chunk counts): wave scans now, wave totals combined after the barrier
+  int part = 0;
+  for (int i = tid; i < bh; i += kSelThreads) part += min(max(prm.budgets[i], 0), prm.lens.P[i / prm.H]);
+  part = wave_incl_scan(part, lane);
+  const int cnt = (!POOL && kh > 0 && tid < nch) ? prm.cand_cnt[(int64_t)bh * prm.max_chunks + tid] : 0;
+  const int cincl = wave_incl_scan(cnt, lane);
+  if (lane == 63) {
+    wsum[wave][0] = part;
+    wsum[wave][1] = cincl;
+  }
+  for (int i = tid; i < kHistWords; i += kSelThreads) hist[i] = 0;
+  __syncthreads();
+  int base = 0, cbefore = 0;
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) {
+    base += wsum[w][0];
+    if (w < wave) cbefore += wsum[w][1];
+  }
+  if (tid == 0) {
+    prm.cu[bh] = base;
+    if (bh == prm.BH - 1) prm.cu[prm.BH] = base + kh;
+    coff[0] = 0;
+  }
+  if (kh == 0) return;
+  if (!POOL && tid < nch) coff[tid + 1] = cbefore + cincl;
+  __syncthreads();
+
+  const int n = POOL ? P : coff[nch];
+  const bool in_lds = n <= prm.lds_words;
+  // candidate e of the head sits in chunk c = the last one with coff[c] <= e
+  auto slot_of = [&](int e) -> int64_t {
+    int a = 0, z = nch;  // coff[a] <= e < coff[z]
+    while (z - a > 1) {
+      const int m = (a + z) >> 1;
+      if (coff[m] <= e)
+        a = m;
+      else
+        z = m;
+    }
+    return head_ws + (int64_t)a * kChunk + (e - coff[a]);
+  };
+  auto key_at = [&](int e) -> uint32_t { return in_lds ? lds_keys[e] : prm.cand_key[slot_of(e)]; };
+
+  // ---- the keys (into LDS when they fit) and their range
+  uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+  uint32_t pkey[4] = {0u, 0u, 0u, 0u};  // POOL: this thread's four consecutive keys (n <= 4096)
+  if (POOL) {
+    pooled_keys4(prm.scores + (int64_t)bh * prm.score_stride, 4 * tid, P, (prm.window - 1) / 2, prm.mode, pkey);
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (4 * tid + e < n) {
+        lds_keys[4 * tid + e] = pkey[e];
+        kmin = min(kmin, pkey[e]);
+        kmax = max(kmax, pkey[e]);
+      }
+  } else {
+    // four independent loads in flight per thread (the chunks' candidate lists are read as one flat list)
+    for (int e0 = 0; e0 < n; e0 += 4 * kSelThreads) {
+      uint32_t kk[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int e = e0 + u * kSelThreads + tid;
+        kk[u] = e < n ? prm.cand_key[slot_of(e)] : 0u;
       }
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) tmin = min(tmin, (uint32_t)__shfl_xor((int)tmin, o, 64));
-    if (lane == 0) wmin[wave] = tmin;
-    __syncthreads();
-    if (tid == 0) {
-      uint32_t lo = wmin[0];
-      for (int w = 1; w < kSelWaves; ++w) lo = min(lo, wmin[w]);
-      sh_lo = lo;
-      sh_hi = all_hi;
-      sh_krem = k;
-      sh_nlist = kSelThreads * c;
+      for (int u = 0; u < 4; ++u) {
+        const int e = e0 + u * kSelThreads + tid;
+        if (e < n) {
+          if (in_lds) lds_keys[e] = kk[u];
+          kmin = min(kmin, kk[u]);
+          kmax = max(kmax, kk[u]);
+        }
+      }
     }
-    __syncthreads();
-    refine(1);  // one round is enough here: the lower edge of the chosen bin is a lower bound as well
-    const uint32_t t0 = sh_lo;
-    __syncthreads();  // everyone has read t0 and is done with the remembered keys
-    if (tid == 0) sh_nlist = 0;
-    __syncthreads();
+  }
+  kmin = wave_min(kmin);
+  kmax = wave_max(kmax);
+  if (lane == 0) {
+    wmin[wave] = kmin;
+    wmax[wave] = kmax;
+  }
+  __syncthreads();
+  uint32_t lo = wmin[0], hi = wmax[0];
+#pragma unroll
+  for (int w = 1; w < kSelWaves; ++w) {
+    lo = min(lo, wmin[w]);
+    hi = max(hi, wmax[w]);
+  }
+  int krem = kh;
+
+  // ---- range refinement until a single key remains (three rounds at most; the bound is only a guard)
+  for (int round = 0; round < 4 && lo != hi; ++round) {
+    const Round rd(lo, hi);
     for (int e0 = 0; e0 < n; e0 += kSelThreads) {
       const int e = e0 + tid;
       const uint32_t key = e < n ? key_at(e) : 0u;
-      const bool cand = e < n && key >= t0;
-      const uint64_t m = __ballot(cand);
-      if (m) {
-        const int leader = __ffsll((unsigned long long)m) - 1;
-        int pos = 0;
-        if (lane == leader) pos = atomicAdd(&sh_nlist, __popcll(m));
-        pos = __shfl(pos, leader, 64) + __popcll(m & ((1ull << lane) - 1ull));
-        if (cand && pos < kListCap) list[pos] = key;
-      }
+      const bool cand = e < n && key >= lo && key <= hi;
+      vote(hist, cand, cand ? rd.top_bin(key) : 0, lane);
     }
     __syncthreads();
-    short_list = sh_nlist <= kListCap;
+    if (wave == 0) pick_bin(hist, rd, hi, krem, lane, &st);
     __syncthreads();
-    if (tid == 0) {
-      sh_lo = short_list ? t0 : all_lo;
-      sh_hi = all_hi;
-      sh_krem = k;
-      if (!short_list) sh_nlist = -1;
-    }
-    __syncthreads();
+    lo = st.lo;
+    hi = st.hi;
+    krem = st.krem;
   }
-  refine(4);
-  const uint32_t tau = sh_lo;
-  const int need_eq = sh_krem;  // how many entries equal to tau are kept (lowest first)
+  const uint32_t tau = lo;
+  const int need_eq = krem;  // how many entries equal to tau are kept (lowest positions first)
 
   // ---- ordered emit: wave w owns entries [w*seg, (w+1)*seg)
   const int seg = ((n + kSelWaves - 1) / kSelWaves + 63) / 64 * 64;
@@ -402,12 +437,20 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
   }
   __syncthreads();
   int gt_before = 0, eq_before = 0;
-  for (int w = 0; w < wave; ++w) {
-    gt_before += wsum[w][0];
-    eq_before += wsum[w][1];
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) {
+    if (w < wave) {
+      gt_before += wsum[w][0];
+      eq_before += wsum[w][1];
+    }
   }
-  const int64_t room = prm.capacity - base;  // final stage: rows of idx this head may write
-  const int64_t chunk_ws = head_ws + (int64_t)blockIdx.y * kChunk;  // chunk stage: this chunk's candidates
+  const int64_t room = prm.capacity - base;  // rows of idx this head may write
+  const int rows = (int)min((int64_t)kh, max(room, (int64_t)0));
+  // The kept candidates' positions sit in global memory.  When there is room behind the keys, the kept entry
+  // numbers first go to an LDS list in output order, and the positions are then fetched with independent loads
+  // (one per thread) instead of one dependent load per step of a wave's slice.
+  const bool listed = !POOL && in_lds && n + kh <= prm.lds_words;
+  uint32_t* kept = lds_keys + n;
   for (int e0 = s0; e0 < s1; e0 += 64) {
     const int e = e0 + lane;
     const uint32_t kv = e < s1 ? key_at(e) : 0u;
@@ -416,20 +459,27 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const SelectParams 
     const uint64_t mgt = __ballot(gt);
     const uint64_t meq = __ballot(eq);
     const uint64_t below = (1ull << lane) - 1ull;
-    const int pg = __popcll(mgt & below);
-    const int pe = __popcll(meq & below);
-    const int eq_rank = eq_before + pe;
+    const int eq_rank = eq_before + __popcll(meq & below);
     if (gt || (eq && eq_rank < need_eq)) {
-      const int pos = gt_before + pg + min(eq_rank, need_eq);
-      if (FINAL) {
-        if (pos < room) prm.idx[base + pos] = POOL ? c0 + e : prm.cand_pos[cand_slot(e)];
-      } else {
-        prm.cand_key[chunk_ws + pos] = kv;
-        prm.cand_pos[chunk_ws + pos] = c0 + e;
+      const int pos = gt_before + __popcll(mgt & below) + min(eq_rank, need_eq);
+      if (pos < rows) {
+        if (POOL)
+          prm.idx[base + pos] = e;
+        else if (listed)
+          kept[pos] = (uint32_t)e;
+        else
+          prm.idx[base + pos] = prm.cand_pos[slot_of(e)];
       }
     }
     gt_before += __popcll(mgt);
     eq_before += __popcll(meq);
+  }
+  if (listed) {
+    __syncthreads();
+    for (int rr = tid; rr < rows; rr += kSelThreads) {
+      const int pos = prm.cand_pos[slot_of((int)kept[rr])];
+      prm.idx[base + rr] = pos;
+    }
   }
 }
 
@@ -462,28 +512,23 @@ __global__ __launch_bounds__(256) void head_budgets_kernel(const BudgetParams pr
   }
 }
 
-bool select_uses_lds(const maskkv_desc* d) { return d->P_max <= kSelLdsCap; }
+int64_t select_chunks(const maskkv_desc* d) { return ((int64_t)d->P_max + kChunk - 1) / kChunk; }
 
-int64_t select_cand_slots(const maskkv_desc* d) {
-  const int64_t max_chunks = (d->P_max + kChunk - 1) / kChunk;
-  return (int64_t)d->B * d->H * max_chunks * kChunk;
-}
+int64_t select_cand_slots(const maskkv_desc* d) { return (int64_t)d->B * d->H * select_chunks(d) * kChunk; }
 
-template <typename K>
-int raise_lds_limit(K kernel, size_t bytes) {
-  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-  if (e == hipSuccess) return MASKKV_OK;
-  set_error("select: cannot raise dynamic LDS limit: %s", hipGetErrorString(e));
-  (void)hipGetLastError();
-  return MASKKV_EHIP;
+size_t select_count_bytes(const maskkv_desc* d) {
+  return ((size_t)((int64_t)d->B * d->H * select_chunks(d)) * sizeof(int32_t) + 255) / 256 * 256;
 }
 
 }  // namespace
 
-// The (key, position) candidates that the chunk stage hands to the final stage.
+// Longest prompt the final stage can index (its chunk offsets live in LDS).
+int64_t select_max_prompt() { return (int64_t)kMaxChunks * kChunk; }
+
+// The (key, position) candidates that the chunk stage hands to the final stage, and their count per chunk.
 size_t select_workspace_bytes(const maskkv_desc* d) {
-  return (size_t)select_cand_slots(d) * (sizeof(uint32_t) + sizeof(int32_t));
+  if (select_chunks(d) <= 1) return 0;  // single-chunk prompts are selected in one kernel
+  return (size_t)select_cand_slots(d) * (sizeof(uint32_t) + sizeof(int32_t)) + select_count_bytes(d);
 }
 
 int launch_select(const maskkv_desc* d, const Lens& lens, const float* scores, int64_t score_stride, int window,
@@ -502,33 +547,35 @@ int launch_select(const maskkv_desc* d, const Lens& lens, const float* scores, i
   prm.idx = idx;
   prm.cu = cu_budget;
   prm.capacity = capacity;
-  prm.max_chunks = (d->P_max + kChunk - 1) / kChunk;
+  prm.max_chunks = (int)select_chunks(d);
   prm.cand_key = reinterpret_cast<uint32_t*>(workspace);
   prm.cand_pos = reinterpret_cast<int32_t*>(prm.cand_key + select_cand_slots(d));
-  if (prm.max_chunks == 1) {  // every prompt fits one chunk: pool, select and emit in a single kernel
-    hipLaunchKernelGGL((select_kernel<true, true, true>), dim3(prm.BH), dim3(kSelThreads), kChunk * sizeof(uint32_t),
-                       stream, prm);
+  prm.cand_cnt = prm.cand_pos + select_cand_slots(d);
+  prm.lds_words = (int)min((int64_t)kSelLdsCap, ((int64_t)max(d->P_max, 1) + 63) / 64 * 64);
+  const size_t dyn = (size_t)prm.lds_words * sizeof(uint32_t);
+  static bool granted = false;  // one-time opt-in to more than the default dynamic LDS size
+  if (!granted) {
+    const size_t want = (size_t)kSelLdsCap * sizeof(uint32_t);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_final_kernel<false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)want);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_final_kernel<true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)want);
+    if (e != hipSuccess) {
+      set_error("select: cannot raise dynamic LDS limit: %s", hipGetErrorString(e));
+      (void)hipGetLastError();
+      return MASKKV_EHIP;
+    }
+    granted = true;
+  }
+  if (prm.max_chunks <= 1) {  // every prompt fits one chunk: pool, select and emit in a single kernel
+    hipLaunchKernelGGL((select_final_kernel<true>), dim3(prm.BH), dim3(kSelThreads), dyn, stream, prm);
     return check_launch("select (single stage)");
   }
-  if (prm.max_chunks > 0) {
-    hipLaunchKernelGGL((select_kernel<false, true, true>), dim3(prm.BH, prm.max_chunks), dim3(kSelThreads),
-                       kChunk * sizeof(uint32_t), stream, prm);
-    if (int e = check_launch("select (chunk stage)")) return e;
-  }
-  if (select_uses_lds(d)) {
-    const size_t dyn = (size_t)((d->P_max + 63) / 64 * 64) * sizeof(uint32_t);
-    if (dyn > 48 * 1024) {
-      static thread_local bool granted = false;  // one-time opt-in to more than the default dynamic LDS size
-      if (!granted) {
-        if (int e = raise_lds_limit(&select_kernel<true, true, false>, kSelLdsCap * sizeof(uint32_t))) return e;
-        granted = true;
-      }
-    }
-    hipLaunchKernelGGL((select_kernel<true, true, false>), dim3(prm.BH), dim3(kSelThreads), dyn, stream, prm);
-  } else {
-    hipLaunchKernelGGL((select_kernel<true, false, false>), dim3(prm.BH), dim3(kSelThreads), 0, stream, prm);
-  }
-  return check_launch("select");
+  hipLaunchKernelGGL(select_chunk_kernel, dim3(prm.BH, prm.max_chunks), dim3(kSelThreads), 0, stream, prm);
+  if (int e = check_launch("select (chunk stage)")) return e;
+  hipLaunchKernelGGL((select_final_kernel<false>), dim3(prm.BH), dim3(kSelThreads), dyn, stream, prm);
+  return check_launch("select (final stage)");
 }
 
 int launch_head_budgets(const maskkv_desc* d, const float* prompt_mass, int32_t k_l, float alpha, int32_t* budgets,

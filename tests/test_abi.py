@@ -48,7 +48,7 @@ def test_strerror(mk):
 def test_workspace_sizes(mk):
     d = mk.Desc(B=1, H=32, d=128, dtype=mk.MASKKV_BF16, n_resp=256, P_max=32768)
     assert mk.maskkv_score_workspace_bytes(d) > 32 * 256 * 4
-    assert mk.maskkv_select_workspace_bytes(d) == 32 * 32768 * 8  # (key, position) candidates, 4096 per chunk
+    assert mk.maskkv_select_workspace_bytes(d) == 32 * 32768 * 8 + 32 * 8 * 4  # candidates (4096 per chunk) + counts
     assert mk.maskkv_attend_workspace_bytes(d, False) == 0
     assert mk.maskkv_attend_workspace_bytes(d, True) > 0
     grouped = mk.Desc(B=1, H=4, d=128, dtype=mk.MASKKV_BF16, n_resp=256, P_max=32768, q_per_kv=7)
@@ -57,7 +57,7 @@ def test_workspace_sizes(mk):
     assert mk.maskkv_score_workspace_bytes(grouped) > mk.maskkv_score_workspace_bytes(single) + 4 * 7 * 32768 * 4
     assert mk.maskkv_select_workspace_bytes(grouped) == mk.maskkv_select_workspace_bytes(single)   # per KV head
     long = mk.Desc(B=2, H=4, d=128, dtype=mk.MASKKV_BF16, n_resp=8, P_max=100000)
-    assert mk.maskkv_select_workspace_bytes(long) == 2 * 4 * 25 * 4096 * 8
+    assert mk.maskkv_select_workspace_bytes(long) == 2 * 4 * 25 * 4096 * 8 + 1024   # 800 bytes of counts, padded to 256 B
 
 
 @pytest.mark.parametrize("kw,status", [
@@ -97,7 +97,7 @@ def test_bad_call_arguments_are_rejected_before_launch(mk):
     assert call_score(good, good, 128, f, 16) == 4              # too small
     assert call_score(good, good, 128, ct.c_void_p(fake + 8), 1 << 20) == 4  # misaligned workspace
     sel = lambda window, mode, cap: lib.maskkv_select(
-        ct.byref(desc), f, ct.c_int64(128), ct.c_int(window), ct.c_int(mode), f, f, f, ct.c_int64(cap), None,
+        ct.byref(desc), f, ct.c_int64(128), ct.c_int(window), ct.c_int(mode), f, None, f, f, ct.c_int64(cap), None,
         ct.c_size_t(0), None)
     assert sel(4, 0, 10) == 1      # even window
     assert sel(0, 0, 10) == 1
@@ -155,3 +155,28 @@ def test_layer_budgets_host_arithmetic_matches_the_oracle(mk):
                                        ct.c_size_t(1 << 20), None) == 1     # hidden not a multiple of 8
     assert lib.maskkv_layer_importance(f, f, ct.c_int64(10), ct.c_int32(128), ct.c_int32(1), ct.c_int64(128), f, None,
                                        ct.c_size_t(0), None) == 4           # no workspace
+
+
+def test_select_checks_a_host_copy_of_the_budgets_before_launch(mk):
+    """With the optional host copy of the budgets a negative budget is MASKKV_EINVAL and budgets that keep more rows
+    than the capacity are MASKKV_ECAPACITY; both before anything is enqueued (the pointers here are fake)."""
+    lib = mk.raw_library()
+    desc = mk.Desc(B=2, H=2, d=64, dtype=mk.MASKKV_F32, n_resp=8, P_max=100, prompt_len=[100, 40]).c()
+    f = ct.c_void_p(0x1000)
+
+    def sel(host, cap):
+        arr = (ct.c_int32 * 4)(*host)
+        return lib.maskkv_select(ct.byref(desc), f, ct.c_int64(128), ct.c_int(7), ct.c_int(0), f, arr, f, f,
+                                 ct.c_int64(cap), None, ct.c_size_t(0), None)
+    assert sel([10, -1, 5, 5], 100) == 1
+    assert b"negative" in lib.maskkv_last_error()
+    assert sel([10, 20, 30, 1000], 99) == 6          # clamped to the prompts: 10 + 20 + 30 + 40 = 100 > 99
+    assert b"capacity" in lib.maskkv_last_error()
+    assert lib.maskkv_strerror(6) == b"output capacity too small"
+    # prompts beyond what the final stage can index, and offsets beyond 31 bits
+    big = mk.Desc(B=1, H=2, d=64, dtype=mk.MASKKV_F32, n_resp=8, P_max=(1 << 22) + 1).c()
+    assert lib.maskkv_select(ct.byref(big), f, ct.c_int64(1 << 23), ct.c_int(7), ct.c_int(0), f, None, f, f,
+                             ct.c_int64(10), f, ct.c_size_t(1 << 40), None) == 2
+    wide = mk.Desc(B=64, H=1024, d=64, dtype=mk.MASKKV_F32, n_resp=8, P_max=1 << 20).c()
+    assert lib.maskkv_select(ct.byref(wide), f, ct.c_int64(1 << 20), ct.c_int(7), ct.c_int(0), f, None, f, f,
+                             ct.c_int64(10), f, ct.c_size_t(1 << 40), None) == 2

@@ -206,7 +206,7 @@ def test_select_long_prompt_reads_candidates_in_place():
     rng = np.random.default_rng(6)
     P = 50000
     desc = m.Desc(B=1, H=2, d=128, dtype=m.MASKKV_BF16, n_resp=8, P_max=P)
-    assert m.maskkv_select_workspace_bytes(desc) == 2 * 13 * 4096 * 8
+    assert m.maskkv_select_workspace_bytes(desc) == 2 * 13 * 4096 * 8 + 256   # candidates + their counts per chunk
     sc = (rng.random((2, P)) ** 4).astype(np.float32)
     budgets = np.array([1234, 40000], dtype=np.int32)
     idx = torch.full((int(budgets.sum()),), -1, dtype=torch.int32, device="cuda")
