@@ -133,16 +133,6 @@ int maskkv_score(const maskkv_desc* desc, const maskkv_tensor* Q_mask, const mas
                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * maskkv_score with timing marks.  events: HOST array of 4 hipEvent_t (each may be NULL), created by
- * the caller with timing enabled; they are recorded on the stream before pass 1 (row statistics),
- * before the merge, before pass 2 (column sums) and after pass 2.  Same result as maskkv_score.
- * For profiling harnesses; Section 3.3 Stage 1 as above.
- */
-int maskkv_score_profiled(const maskkv_desc* desc, const maskkv_tensor* Q_mask, const maskkv_tensor* K_full,
-                          float scale, float* scores, int64_t score_stride, float* prompt_mass,
-                          void* workspace, size_t workspace_bytes, void* stream, void* const* events);
-
-/*
  * maskkv_score for callers that cannot allocate device memory or carry a workspace: code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc.  Same arguments and same result as maskkv_score, but the
  * scratch between the passes lives in an array of MASKKV_STATIC_SCRATCH_BYTES that is part of the library image
@@ -276,23 +266,6 @@ int maskkv_layer_budgets(const float* importance, int32_t n_layers, int64_t k_p,
  */
 int maskkv_value_shift(const void* V_now, const void* V_prev, int64_t n_tokens, int32_t width, int32_t dtype,
                        int64_t row_stride, float delta, float* cos, int32_t* refresh, int32_t* count, void* stream);
-
-/*
- * Measurement probe (not part of the method; for roofline harnesses): enqueues one kernel that exercises a
- * single resource, so that the caller can time it and quote kernel rates against what this chip sustains.
- *   which = 0  bf16 matrix pipe: every wave of `groups` 256-thread workgroups issues 4*iters
- *              v_mfma_f32_32x32x16_bf16 from registers;      *work = floating-point operations
- *   which = 1  v_exp_f32: every lane issues 8*iters exponentials;               *work = exponentials
- *   which = 2  streaming copy of `bytes` from src to dst (grid-stride, 16-byte pieces); *work = bytes read + written
- *   which = 3  streaming read of `bytes` from src (folded into one word per thread);     *work = bytes read
- *   which = 4  the scoring kernels' instruction mix from registers: per iteration every wave issues 16 MFMAs and
- *              every lane 32 x (fma, v_exp_f32, add);                    *work = floating-point operations of the MFMAs
- * dst: DEVICE of dst_bytes bytes; for which != 2 it receives groups*256 32-bit words, for which = 2 it is the copy
- * target.  src: DEVICE, 16-byte aligned, `bytes` a multiple of 16 (which >= 2; ignored otherwise).  work: HOST
- * double, may be NULL.  groups: 256-thread workgroups launched, 1..2^20.  MASKKV_EINVAL on any violation.
- */
-int maskkv_probe(int which, int32_t iters, const void* src, void* dst, int64_t bytes, int64_t dst_bytes,
-                 int32_t groups, void* stream, double* work);
 
 #ifdef __cplusplus
 }

@@ -24,13 +24,13 @@ MAX_BATCH = 64
 
 SYMBOLS = [
     "maskkv_version", "maskkv_strerror", "maskkv_last_error",
-    "maskkv_score_workspace_bytes", "maskkv_score", "maskkv_score_profiled", "maskkv_score_static",
+    "maskkv_score_workspace_bytes", "maskkv_score", "maskkv_score_static",
     "maskkv_select_workspace_bytes", "maskkv_select",
     "maskkv_compact",
     "maskkv_attend_workspace_bytes", "maskkv_attend", "maskkv_attend_full",
     "maskkv_head_budgets",
     "maskkv_layer_importance_workspace_bytes", "maskkv_layer_importance", "maskkv_layer_budgets",
-    "maskkv_value_shift", "maskkv_probe",
+    "maskkv_value_shift",
 ]
 
 
@@ -174,18 +174,6 @@ def maskkv_score_static(desc: Desc, Q_mask, K_full, scale: float, scores: torch.
            "maskkv_score_static")
 
 
-def maskkv_score_profiled(desc: Desc, Q_mask, K_full, scale: float, scores: torch.Tensor, score_stride: int,
-                          prompt_mass: Optional[torch.Tensor], workspace: Optional[torch.Tensor], events: Sequence[int],
-                          stream=None) -> None:
-    """``events``: four raw hipEvent_t handles (0 to skip one), recorded at the stage boundaries."""
-    q, k = _as_view(Q_mask), _as_view(K_full)
-    wp, wn = _ws(workspace)
-    ev = (ct.c_void_p * 4)(*[ct.c_void_p(int(e)) for e in events])
-    _check(_lib.maskkv_score_profiled(ct.byref(desc.c()), ct.byref(q), ct.byref(k), ct.c_float(scale), _ptr(scores),
-                                      ct.c_int64(score_stride), _ptr(prompt_mass), wp, wn, _stream(stream), ev),
-           "maskkv_score_profiled")
-
-
 def _host_i32(values: Optional[Sequence[int]]):
     if values is None:
         return None
@@ -275,18 +263,6 @@ def maskkv_value_shift(V_now: torch.Tensor, V_prev: torch.Tensor, delta: float, 
     _check(_lib.maskkv_value_shift(_ptr(V_now), _ptr(V_prev), ct.c_int64(V_now.shape[0]), ct.c_int32(V_now.shape[1]),
                                    ct.c_int32(_dtype_code(V_now)), ct.c_int64(V_now.stride(0)), ct.c_float(delta),
                                    _ptr(cos), _ptr(refresh), _ptr(count), _stream(stream)), "maskkv_value_shift")
-
-
-def maskkv_probe(which: int, iters: int, src: Optional[torch.Tensor], dst: torch.Tensor, groups: int,
-                 stream=None) -> float:
-    """Enqueue a measurement probe (0 matrix pipe, 1 v_exp_f32, 2 streaming copy src -> dst, 3 streaming read of
-    src, 4 the scoring kernels' instruction mix); returns the work it does (flops, exponentials or bytes moved)."""
-    work = ct.c_double(0.0)
-    nbytes = src.numel() * src.element_size() if src is not None else 0
-    _check(_lib.maskkv_probe(ct.c_int(which), ct.c_int32(iters), _ptr(src) if src is not None else None, _ptr(dst),
-                             ct.c_int64(nbytes), ct.c_int64(dst.numel() * dst.element_size()), ct.c_int32(groups),
-                             _stream(stream), ct.byref(work)), "maskkv_probe")
-    return float(work.value)
 
 
 def raw_library() -> ct.CDLL:

@@ -1,4 +1,5 @@
-"""Build libmaskkv.so (HIP, gfx950) in-tree with hipcc."""
+"""Build the HIP libraries (gfx950) in-tree with hipcc: libmaskkv.so (the product) and libmaskkv_bench.so
+(measurement probes and stage marks for benchmark harnesses; it links against the product library)."""
 from __future__ import annotations
 
 import os
@@ -7,7 +8,9 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmaskkv.so")
-SOURCES = ["api.hip", "score.hip", "select.hip", "compact.hip", "attend.hip", "layer.hip", "probe.hip"]
+BENCH_LIB = os.path.join(HERE, "libmaskkv_bench.so")
+SOURCES = ["api.hip", "score.hip", "select.hip", "compact.hip", "attend.hip", "layer.hip"]
+BENCH_SOURCES = [os.path.join("bench", "probe.hip")]
 FLAGS = [
     "-shared", "-fPIC", "-O3", "-std=c++17", "--offload-arch=gfx950",
     # packed fp32 arithmetic is kept off for every kernel in this library
@@ -17,16 +20,22 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every kernel file into paper_2510_09309_amd/libmaskkv.so; returns the path."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB + ".tmp"]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+
+
+def build(verbose: bool = False) -> str:
+    """Compile every kernel file into paper_2510_09309_amd/libmaskkv.so (+ libmaskkv_bench.so); returns the product's path."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    _run([hipcc] + FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB + ".tmp"], verbose)
     os.replace(LIB + ".tmp", LIB)
+    _run([hipcc] + FLAGS + [os.path.join(CSRC, s) for s in BENCH_SOURCES] +
+         ["-L" + HERE, "-l:libmaskkv.so", "-Wl,-rpath,$ORIGIN", "-o", BENCH_LIB + ".tmp"], verbose)
+    os.replace(BENCH_LIB + ".tmp", BENCH_LIB)
     return LIB
 
 

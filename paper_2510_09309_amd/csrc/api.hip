@@ -160,6 +160,28 @@ int static_scratch(void** ptr) {
 }  // namespace
 }  // namespace maskkv
 
+namespace maskkv {
+
+// maskkv_score with optional stage marks (see kernels.hpp).
+int score_entry(const maskkv_desc* desc, const maskkv_tensor* Q_mask, const maskkv_tensor* K_full, float scale,
+                float* scores, int64_t score_stride, float* prompt_mass, void* workspace, size_t workspace_bytes,
+                void* stream, void* const* events) {
+  Lens lens;
+  View q, k;
+  if (int e = check_desc(desc, &lens)) return e;
+  if (int e = make_view(desc, Q_mask, "Q_mask", &q)) return e;
+  if (int e = make_view(desc, K_full, "K_full", &k)) return e;
+  if (!scores || score_stride < desc->P_max) {
+    set_error("scores is NULL or score_stride %lld < P_max %d", (long long)score_stride, desc->P_max);
+    return MASKKV_EINVAL;
+  }
+  if (int e = check_workspace("score", workspace, workspace_bytes, score_workspace_bytes(desc, lens))) return e;
+  return launch_score(desc, q, k, lens, pick_scale(desc, scale), scores, score_stride, prompt_mass, workspace,
+                      reinterpret_cast<hipStream_t>(stream), events);
+}
+
+}  // namespace maskkv
+
 using namespace maskkv;
 
 extern "C" {
@@ -195,25 +217,8 @@ int maskkv_score_workspace_bytes(const maskkv_desc* desc, size_t* bytes) {
 int maskkv_score(const maskkv_desc* desc, const maskkv_tensor* Q_mask, const maskkv_tensor* K_full, float scale,
                  float* scores, int64_t score_stride, float* prompt_mass, void* workspace, size_t workspace_bytes,
                  void* stream) {
-  return maskkv_score_profiled(desc, Q_mask, K_full, scale, scores, score_stride, prompt_mass, workspace,
-                               workspace_bytes, stream, nullptr);
-}
-
-int maskkv_score_profiled(const maskkv_desc* desc, const maskkv_tensor* Q_mask, const maskkv_tensor* K_full,
-                          float scale, float* scores, int64_t score_stride, float* prompt_mass, void* workspace,
-                          size_t workspace_bytes, void* stream, void* const* events) {
-  Lens lens;
-  View q, k;
-  if (int e = check_desc(desc, &lens)) return e;
-  if (int e = make_view(desc, Q_mask, "Q_mask", &q)) return e;
-  if (int e = make_view(desc, K_full, "K_full", &k)) return e;
-  if (!scores || score_stride < desc->P_max) {
-    set_error("scores is NULL or score_stride %lld < P_max %d", (long long)score_stride, desc->P_max);
-    return MASKKV_EINVAL;
-  }
-  if (int e = check_workspace("score", workspace, workspace_bytes, score_workspace_bytes(desc, lens))) return e;
-  return launch_score(desc, q, k, lens, pick_scale(desc, scale), scores, score_stride, prompt_mass, workspace,
-                      reinterpret_cast<hipStream_t>(stream), events);
+  return score_entry(desc, Q_mask, K_full, scale, scores, score_stride, prompt_mass, workspace, workspace_bytes,
+                     stream, nullptr);
 }
 
 int maskkv_score_static(const maskkv_desc* desc, const maskkv_tensor* Q_mask, const maskkv_tensor* K_full, float scale,
@@ -444,36 +449,6 @@ int maskkv_value_shift(const void* V_now, const void* V_prev, int64_t n_tokens, 
   }
   return launch_value_shift(V_now, V_prev, n_tokens, width, dtype, row_stride * eb, delta, cos, refresh, count,
                             reinterpret_cast<hipStream_t>(stream));
-}
-
-int maskkv_probe(int which, int32_t iters, const void* src, void* dst, int64_t bytes, int64_t dst_bytes,
-                 int32_t groups, void* stream, double* work) {
-  if (which < 0 || which > 4 || !dst || groups < 1 || groups > (1 << 20)) {
-    set_error("probe: which %d outside 0..4, dst NULL or groups %d outside 1..2^20", which, groups);
-    return MASKKV_EINVAL;
-  }
-  if (which != 2 && dst_bytes < (int64_t)groups * 256 * 4) {
-    set_error("probe: dst of %lld bytes is smaller than groups*256 words", (long long)dst_bytes);
-    return MASKKV_EINVAL;
-  }
-  if (which < 2 || which == 4) {
-    if (iters < 1) {
-      set_error("probe: iters %d < 1", iters);
-      return MASKKV_EINVAL;
-    }
-    // floating-point operations (which = 0: 2*32*32*16 per MFMA, 4 waves x 4 MFMAs per iteration) or exponentials
-    if (work)
-      *work = which == 1 ? (double)groups * 256 * 8 * iters
-                         : (double)groups * 4 * (which == 0 ? 4 : 16) * iters * 32768.0;
-  } else {
-    if (!src || bytes < 16 || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15) ||
-        (which == 2 && dst_bytes < bytes)) {
-      set_error("probe: streaming needs 16-byte aligned src and dst, a positive multiple of 16 bytes, and room in dst");
-      return MASKKV_EINVAL;
-    }
-    if (work) *work = which == 2 ? 2.0 * (double)bytes : (double)bytes;  // bytes read (+ written)
-  }
-  return launch_probe(which, iters, src, dst, bytes, groups, reinterpret_cast<hipStream_t>(stream));
 }
 
 int maskkv_layer_budgets(const float* importance, int32_t n_layers, int64_t k_p, float beta, const int32_t* boundary,

@@ -37,7 +37,11 @@ int launch_layer_importance(const void* h_in, const void* h_out, int64_t n, int 
 int launch_value_shift(const void* v_now, const void* v_prev, int64_t n, int width, int dtype, int64_t row_bytes,
                        float delta, float* cos, int32_t* refresh, int32_t* count, hipStream_t stream);
 
-// probe.hip: which = 0 matrix pipe, 1 v_exp_f32, 2 streaming copy, 3 streaming read, 4 scoring instruction mix
-int launch_probe(int which, int iters, const void* src, void* dst, int64_t bytes, int groups, hipStream_t stream);
+// api.hip: the body of maskkv_score.  events: null, or four hipEvent_t (each may be null) recorded on the stream
+// before pass 1, before the merge, before pass 2 and after pass 2; measurement harnesses link against this to time
+// the stages of one call (the C entry point always passes null).
+int score_entry(const maskkv_desc* desc, const maskkv_tensor* Q_mask, const maskkv_tensor* K_full, float scale,
+                float* scores, int64_t score_stride, float* prompt_mass, void* workspace, size_t workspace_bytes,
+                void* stream, void* const* events);
 
 }  // namespace maskkv

@@ -38,6 +38,38 @@ def test_library_exports_every_declared_symbol(mk):
     assert mk.maskkv_version() == 1
 
 
+def test_bench_library_exports_its_header_and_rejects_bad_probes():
+    """libmaskkv_bench.so (measurement probes, stage marks) is a library of its own with a header of its own."""
+    from paper_2510_09309_amd import bench_binding as bb
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "maskkv_bench.h")).read(), flags=re.S)
+    names = sorted(set(re.findall(r"\b(maskkv_bench_[a-z_]+)\s*\(", text)))
+    assert names == sorted(bb.SYMBOLS)
+    lib = ct.CDLL(bb.LIB_PATH)
+    for name in names:
+        assert hasattr(lib, name)
+    f = ct.c_void_p(0x1000)
+    probe = lambda which, iters, src, nbytes, dst_bytes, groups: lib.maskkv_bench_probe(
+        ct.c_int(which), ct.c_int32(iters), src, f, ct.c_int64(nbytes), ct.c_int64(dst_bytes), ct.c_int32(groups), None,
+        None)
+    assert probe(6, 10, None, 0, 1 << 20, 8) == 1              # unknown probe
+    assert probe(4, 0, None, 0, 1 << 20, 8) == 1               # no iterations
+    assert probe(0, 0, None, 0, 1 << 20, 8) == 1               # no iterations
+    assert probe(0, 10, None, 0, 8 * 256 * 4 - 4, 8) == 1      # result buffer too small
+    assert probe(2, 0, None, 1024, 1024, 8) == 1               # copy without a source
+    assert probe(2, 0, f, 1000, 1024, 8) == 1                  # not a multiple of 16 bytes
+    assert probe(2, 0, f, 2048, 1024, 8) == 1                  # copy target too small
+    assert probe(3, 0, f, 2048, 1024, 8) == 1                  # read: result buffer too small
+    assert probe(5, 10, f, 1024, 1 << 20, 8) == 1              # data-fed matrix probe: operands missing
+    lib.maskkv_bench_last_error.restype = ct.c_char_p
+    assert b"24 KiB" in lib.maskkv_bench_last_error()
+
+
+def test_product_library_exports_no_measurement_entry_points(mk):
+    lib = ct.CDLL(mk.LIB_PATH)
+    for name in ("maskkv_probe", "maskkv_score_profiled", "maskkv_bench_probe", "maskkv_bench_score_marked"):
+        assert not hasattr(lib, name), name
+
+
 def test_strerror(mk):
     lib = mk.raw_library()
     assert lib.maskkv_strerror(0) == b"ok"
@@ -108,17 +140,6 @@ def test_bad_call_arguments_are_rejected_before_launch(mk):
     assert lib.maskkv_head_budgets(ct.byref(desc), f, ct.c_int32(10), ct.c_float(1.5), f, None) == 1
     assert lib.maskkv_head_budgets(ct.byref(desc), f, ct.c_int32(-1), ct.c_float(0.1), f, None) == 1
     assert b"alpha" in lib.maskkv_last_error()
-    probe = lambda which, iters, src, nbytes, dst_bytes, groups: lib.maskkv_probe(
-        ct.c_int(which), ct.c_int32(iters), src, f, ct.c_int64(nbytes), ct.c_int64(dst_bytes), ct.c_int32(groups), None,
-        None)
-    assert probe(5, 10, None, 0, 1 << 20, 8) == 1              # unknown probe
-    assert probe(4, 0, None, 0, 1 << 20, 8) == 1               # no iterations
-    assert probe(0, 0, None, 0, 1 << 20, 8) == 1               # no iterations
-    assert probe(0, 10, None, 0, 8 * 256 * 4 - 4, 8) == 1      # result buffer too small
-    assert probe(2, 0, None, 1024, 1024, 8) == 1               # copy without a source
-    assert probe(2, 0, f, 1000, 1024, 8) == 1                  # not a multiple of 16 bytes
-    assert probe(2, 0, f, 2048, 1024, 8) == 1                  # copy target too small
-    assert probe(3, 0, f, 2048, 1024, 8) == 1                  # read: result buffer too small
     shift = lambda a, b, n, width, dtype, stride, delta: lib.maskkv_value_shift(
         a, b, ct.c_int64(n), ct.c_int32(width), ct.c_int32(dtype), ct.c_int64(stride), ct.c_float(delta), f, f, f, None)
     assert shift(f, None, 10, 64, 0, 64, 0.9) == 1             # NULL input

@@ -68,31 +68,52 @@ def test_importance_feeds_layer_budgets():
 
 
 def test_measurement_probes_run_and_the_copy_is_exact():
-    m = hp.mk()
+    from paper_2510_09309_amd import bench_binding as bb
     out = torch.full((8 * 256,), float("nan"), dtype=torch.float32, device="cuda")
-    flops = m.maskkv_probe(0, 10, None, out, 8)
+    flops = bb.maskkv_bench_probe(0, 10, None, out, 8)
     torch.cuda.synchronize()
     assert flops == 8 * 4 * 4 * 10 * 32768.0 and bool(torch.isfinite(out).all())
     out.fill_(float("nan"))
-    n_exp = m.maskkv_probe(1, 10, None, out, 8)
+    n_exp = bb.maskkv_bench_probe(1, 10, None, out, 8)
     torch.cuda.synchronize()
     assert n_exp == 8 * 256 * 8 * 10 and bool(((out > 0) & (out <= 8)).all())      # eight values in (0, 1] per lane
     out.fill_(float("nan"))
-    assert m.maskkv_probe(4, 10, None, out, 8) == 8 * 4 * 16 * 10 * 32768.0
+    assert bb.maskkv_bench_probe(4, 10, None, out, 8) == 8 * 4 * 16 * 10 * 32768.0
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+    operands = (torch.randn(64 * 24 * 8, device="cuda") / 11.3).to(torch.bfloat16)   # 24 KiB of Gaussian bf16
+    out.fill_(float("nan"))
+    assert bb.maskkv_bench_probe(5, 10, operands, out, 8) == 8 * 4 * 16 * 10 * 32768.0
     torch.cuda.synchronize()
     assert bool(torch.isfinite(out).all())
     src = torch.arange(100003 * 4, dtype=torch.int32, device="cuda")               # a ragged number of 16-byte pieces
     dst = torch.zeros_like(src)
-    moved = m.maskkv_probe(2, 0, src, dst, 7)
+    moved = bb.maskkv_bench_probe(2, 0, src, dst, 7)
     torch.cuda.synchronize()
     assert moved == 2.0 * src.numel() * 4 and torch.equal(src, dst)
     words = torch.zeros(7 * 256, dtype=torch.int32, device="cuda")
-    assert m.maskkv_probe(3, 0, src, words, 7) == src.numel() * 4
+    assert bb.maskkv_bench_probe(3, 0, src, words, 7) == src.numel() * 4
     torch.cuda.synchronize()
-    fold = 0
-    for v in src.cpu().numpy().tolist():
-        fold ^= v
-    got = 0
-    for v in words.cpu().numpy().tolist():
-        got ^= v & 0xFFFFFFFF
-    assert got == fold                                                             # every word was read once
+    fold = int(np.bitwise_xor.reduce(src.cpu().numpy()))
+    assert int(np.bitwise_xor.reduce(words.cpu().numpy())) == fold
+
+
+def test_stage_marks_leave_the_scores_unchanged():
+    """maskkv_bench_score_marked runs the body of maskkv_score: same bits, four ordered events."""
+    from paper_2510_09309_amd import bench_binding as bb
+    from paper_2510_09309_amd import synth
+    m = hp.mk()
+    batch = hp.Batch([synth.make_layer(5, H=2, d=128, P=3000, n_m=64, dtype="bf16", n_planted=10, amplitude=2.5)])
+    want, want_mass = hp.gpu_score(batch)
+    got = torch.full_like(want, float("nan"))
+    mass = torch.full_like(want_mass, float("nan"))
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    for e in ev:
+        e.record()                       # creates the underlying HIP events
+    torch.cuda.synchronize()
+    ws = hp.workspace(m.maskkv_score_workspace_bytes(batch.desc))
+    bb.maskkv_bench_score_marked(batch.desc, batch.Q, batch.K, 0.0, got, got.stride(0), mass, ws,
+                                 [e.cuda_event for e in ev])
+    torch.cuda.synchronize()
+    assert torch.equal(got.view(torch.int32), want.view(torch.int32)) and torch.equal(mass, want_mass)
+    assert ev[0].elapsed_time(ev[1]) > 0 and ev[1].elapsed_time(ev[2]) > 0 and ev[2].elapsed_time(ev[3]) > 0
