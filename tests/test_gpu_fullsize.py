@@ -133,13 +133,29 @@ def test_c3_layers_with_the_layer_budget_schedule(layer):
     budgets = synth.config_budgets("C3", layer)
     assert budgets.sum() == 32 * (512 if layer in (0, 31) else 128)
     batch = hp.Batch([synth.config_layer("C3", layer=layer)])
-    worst, n_band = pipeline_parity(batch, budgets, cfg["window"], heads=[0, 7, 20, 31])
+    heads = [0, 7, 20, 31]
+    worst, n_band = pipeline_parity(batch, budgets, cfg["window"], heads=heads)
+    print(f"C3 layer {layer}: worst score rel err {worst:.2e}, {n_band} kept indices inside the near-tie band")
     assert worst < 1e-4
+    assert n_band <= len(heads)       # near ties are rare: on average at most one swapped pair per head
+
+
+@pytest.mark.parametrize("layer", [0, 15, 31])
+def test_c4_every_head_of_three_layers(layer):
+    """The headline configuration, all 32 heads of the first, a middle and the last layer, every step of the path
+    and the un-evicted attention against the oracle element by element."""
+    from tests.test_gpu_parity import pipeline_parity
+    cfg = synth.CONFIGS["C4"]
+    batch = hp.Batch([synth.config_layer("C4", layer=layer)])
+    worst, n_band = pipeline_parity(batch, synth.config_budgets("C4", layer), cfg["window"])
+    print(f"C4 layer {layer}: worst score rel err {worst:.2e}, {n_band} kept indices inside the near-tie band")
+    assert worst < 1e-4
+    assert n_band <= cfg["H"]
 
 
 def test_c5_full_batch_sampled_heads():
     """The batched ragged configuration at full size (8 sequences x 32 heads, prompts 4k-16k, 512 mask queries,
-    log-uniform budgets), as bench.py's batched block launches it: compression once, then one denoising step with
+    log-uniform budgets), as bench.py's batched block launches it: compression once, then the first, a middle and the last denoising step with
     fresh response Q/K/V; sampled (sequence, head) pairs against the oracle, size-independent properties on all."""
     cfg = synth.CONFIGS["C5"]
     B, H, n_m = cfg["B"], cfg["H"], cfg["n_m"]
@@ -151,9 +167,13 @@ def test_c5_full_batch_sampled_heads():
     idx, cu, cap = hp.gpu_select(batch, scores, budgets, cfg["window"])
     keeps, cu_h = hp.split_idx(idx, cu)
     Kc, Vc = hp.gpu_compact(batch, idx, cu, cap)
-    qkv = [synth.make_response_step(cfg["seed"] + 1 + b, H, cfg["d"], n_m) for b in range(B)]
-    Qr, Kr, Vr = (hp.upload(np.stack([x[i] for x in qkv]), "bf16") for i in range(3))
-    O, lse = hp.gpu_attend(batch, Kc, Vc, cu, cap, Q=Qr, Kr=Kr, Vr=Vr)
+    steps = {}
+    for step in (0, 31, 63):       # first, a middle and the last denoising step: fresh response Q/K/V each
+        qkv = [synth.make_response_step(cfg["seed"] + 1 + 8 * step + b, H, cfg["d"], n_m) for b in range(B)]
+        Qr, Kr, Vr = (hp.upload(np.stack([x[i] for x in qkv]), "bf16") for i in range(3))
+        O, lse = hp.gpu_attend(batch, Kc, Vc, cu, cap, Q=Qr, Kr=Kr, Vr=Vr)
+        assert bool(torch.isfinite(O.float()).all()) and bool(torch.isfinite(lse).all())
+        steps[step] = (qkv, O.float().cpu().numpy(), lse.cpu().numpy().reshape(B, H, n_m))
     # all heads: kept sets have the budgeted size, are ascending and in range; gathered rows are the selected rows
     assert cu_h.tolist() == np.concatenate([[0], np.cumsum(budgets)]).tolist()
     Kc_h = Kc.float().cpu().numpy()
@@ -162,17 +182,19 @@ def test_c5_full_batch_sampled_heads():
             keep = keeps[b * H + h]
             assert keep.size == budgets[b * H + h] and np.all(np.diff(keep) > 0) and 0 <= keep[0] and keep[-1] < L.P
             assert np.array_equal(Kc_h[cu_h[b * H + h]:cu_h[b * H + h + 1]], L.K[h, keep])
-    assert bool(torch.isfinite(O.float()).all()) and bool(torch.isfinite(lse).all())
-    # sampled pairs: every step against the oracle
+    # sampled pairs: compression and the three denoising steps against the oracle
     sc, ms = scores.cpu().numpy(), mass.cpu().numpy()
-    O_h, lse_h = O.float().cpu().numpy(), lse.cpu().numpy().reshape(B, H, n_m)
+    n_band = 0
     for b, h in [(0, 0), (3, 17), (4, 31), (7, 5)]:
         L = layers[b]
         I, m_ref = orc.score(L.Q[h], L.K[h], L.P)
         assert (np.abs(sc[b * H + h, :L.P] - I) / I).max() <= hp.SCORE_RTOL
         assert abs(ms[b * H + h] - m_ref) <= hp.SCORE_RTOL * m_ref
         keep = keeps[b * H + h]
-        hp.check_keep_against_oracle(orc.pool(I, cfg["window"]), int(budgets[b * H + h]), keep, f"b{b} h{h}")
-        ref, rl = orc.attend(qkv[b][0][h], L.K[h, keep], L.V[h, keep], qkv[b][1][h], qkv[b][2][h], return_lse=True)
-        assert np.abs(O_h[b, h] - ref).max() <= hp.ATTEND_ATOL_BF16
-        assert np.abs(lse_h[b, h] - rl).max() <= 1e-3
+        n_band += hp.check_keep_against_oracle(orc.pool(I, cfg["window"]), int(budgets[b * H + h]), keep, f"b{b} h{h}")
+        for step, (qkv, O_h, lse_h) in steps.items():
+            ref, rl = orc.attend(qkv[b][0][h], L.K[h, keep], L.V[h, keep], qkv[b][1][h], qkv[b][2][h], return_lse=True)
+            assert np.abs(O_h[b, h] - ref).max() <= hp.ATTEND_ATOL_BF16, f"step {step} b{b} h{h}"
+            assert np.abs(lse_h[b, h] - rl).max() <= 1e-3, f"step {step} b{b} h{h}"
+    print(f"C5: {n_band} kept indices inside the near-tie band on 4 sampled (sequence, head) pairs")
+    assert n_band <= 4

@@ -243,6 +243,22 @@ def test_pool_float32_mode_is_sequential_single_precision():
         assert y[j] == np.float32(acc / np.float32(hi - lo + 1))
 
 
+def test_pool_max_in_float32_is_exact_and_keeps_the_dtype():
+    """A maximum involves no rounding: in single precision it must return one of the inputs, bit for bit, and agree
+    with the double-precision evaluation of the same float32 values; edges see the clipped window only."""
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal(50).astype(np.float32)
+    y = orc.pool(x, 5, "max", dtype=np.float32)
+    assert y.dtype == np.float32
+    assert np.array_equal(y.astype(np.float64), orc.pool(x.astype(np.float64), 5, "max"))
+    assert np.array_equal(y, np.array(brute_pool(x.tolist(), 5, "max"), dtype=np.float32))
+    for j in (0, 1, 25, 48, 49):
+        assert y[j] == x[max(0, j - 2):min(50, j + 3)].max()
+    spike = np.zeros(9, dtype=np.float32)
+    spike[0], spike[8] = 3.0, -1.0
+    assert orc.pool(spike, 7, "max", dtype=np.float32).tolist() == [3, 3, 3, 3, 0, 0, 0, 0, 0]
+
+
 # --------------------------------------------------------------------------- selection
 @pytest.mark.parametrize("P,k", [(1, 1), (10, 3), (10, 0), (10, 10), (10, 25), (64, 17)])
 def test_select_brute_force(P, k):
@@ -404,6 +420,20 @@ def test_layer_budgets_worked_case():
     k = orc.layer_budgets(np.array([0.3, 0.2, 0.2, 0.3]), k_p=1000, beta=0.4)
     assert k.tolist() == [100 + 180, 100 + 120, 100 + 120, 100 + 180]
     assert k.sum() <= 1000
+
+
+def test_layer_budgets_with_an_explicit_boundary_group():
+    # L = 5, k_p = 1000, beta = 0.5: k_base = floor(500 / 5) = 100, k_imp = 500.  Boundary group = layers {0, 1, 4}
+    # with importance {0.1, 0.2, 0.2} (sum 0.5), middle = layers {2, 3} with {0.25, 0.25} (sum 0.5): each group
+    # receives 250; the boundary layers get floor(250 / 3) = 83 each, the middle layers 125 each.
+    imp = np.array([0.1, 0.2, 0.25, 0.25, 0.2])
+    k = orc.layer_budgets(imp, k_p=1000, beta=0.5, boundary=[0, 1, 4])
+    assert k.tolist() == [183, 183, 225, 225, 183]
+    # the default boundary group is {first, last}: importance {0.1, 0.2} of 1.0 -> 150 for two layers, 350 for three
+    assert orc.layer_budgets(imp, k_p=1000, beta=0.5).tolist() == [175, 100 + 116, 100 + 116, 100 + 116, 175]
+    # duplicates and order in the list do not matter; a boundary group of every layer leaves no middle group
+    assert orc.layer_budgets(imp, 1000, 0.5, boundary=[4, 0, 1, 1]).tolist() == k.tolist()
+    assert orc.layer_budgets(imp, 1000, 0.5, boundary=range(5)).tolist() == [200] * 5
 
 
 def test_layer_importance_closed_forms():
