@@ -35,9 +35,13 @@ struct AttCfg {
   static constexpr int kQPerBlock = kWaves * 32;
   static constexpr int kPieces = kTK * kRowB / 16 / kThreads;
   static constexpr int kSV = kTK + 4;  // elements per transposed-V row (padding keeps LDS reads conflict-free)
+  // bf16: every group of 32 transposed-V rows is shifted by a further 16 bytes.  The fragment reads of a wave stay
+  // inside one group and are unaffected; the transposing stores of a wave touch one row of every group, which
+  // without the shift fall on the same LDS banks four at a time.
+  static constexpr int kVGroupShift = sizeof(T) == 2 ? 16 : 0;
   static constexpr int kDB = D / 32;
   static constexpr int kKtBytes = kTK * kRowP;
-  static constexpr int kVtBytes = D * kSV * (int)sizeof(T);
+  static constexpr int kVtBytes = D * kSV * (int)sizeof(T) + (D / 32) * kVGroupShift;
   static constexpr int kLds = 2 * (kKtBytes + kVtBytes);  // K and V^T tiles, double-buffered
 };
 
@@ -118,8 +122,9 @@ __device__ __forceinline__ void store_kv(char* kt, char* vt, const u32x4 (&kr)[A
         const uint32_t lo = (a[w] & 0xFFFFu) | (bq[w] << 16);
         const uint32_t hi = (a[w] >> 16) | (bq[w] & 0xFFFF0000u);
         const int row = col * 8 + 2 * w;
-        vt32[row * (C::kSV / 2) + pair] = lo;
-        vt32[(row + 1) * (C::kSV / 2) + pair] = hi;
+        const int word = row * (C::kSV / 2) + (row / 32) * (C::kVGroupShift / 4) + pair;  // (row is even)
+        vt32[word] = lo;
+        vt32[word + C::kSV / 2] = hi;
       }
     }
   } else {
@@ -275,7 +280,7 @@ __global__ __launch_bounds__((AttCfg<T, D>::kThreads)) void attend_kernel(const 
             pf[w] = pack_bf16x2(s[kb][8 * tp + 2 * w], s[kb][8 * tp + 2 * w + 1]);
 #pragma unroll
           for (int db = 0; db < C::kDB; ++db) {
-            const char* rowp = vt + ((db * 32 + r) * C::kSV + kb * 32 + 16 * tp + 4 * g) * 2;
+            const char* rowp = vt + ((db * 32 + r) * C::kSV + kb * 32 + 16 * tp + 4 * g) * 2 + db * C::kVGroupShift;
             const u32x2 lo = *reinterpret_cast<const u32x2*>(rowp);
             const u32x2 hi = *reinterpret_cast<const u32x2*>(rowp + 16);
             const u32x4 vf = {lo[0], lo[1], hi[0], hi[1]};
@@ -353,7 +358,8 @@ __global__ __launch_bounds__((AttCfg<T, D>::kThreads)) void attend_kernel(const 
 // loop - and the four partial (O, m, l) are merged through LDS at the end.  Two blocks per wave are kept in
 // flight.  Workgroups of one head are given indices that are congruent modulo 8, which places them on one
 // XCD, so the head's K/V rows are fetched into one L2 only.
-constexpr int kNarrowVS = 36;  // bf16 elements per transposed-V row: 32 keys + padding
+constexpr int kNarrowVS = 36;      // bf16 elements per transposed-V row: 32 keys + padding
+constexpr int kNarrowShift = 16;   // bytes by which every group of 32 rows is shifted further (as in the tiled kernel)
 
 // NW waves per workgroup split the key axis.
 template <int D, int NW>
@@ -364,7 +370,7 @@ struct NarrowCfg {
   static constexpr int kPPR = kRowB / 16;        // 16-byte pieces per row
   static constexpr int kVP = 32 * kPPR / 64;     // V pieces per lane per block
   static constexpr int kDB = D / 32;
-  static constexpr int kVtBytes = D * kNarrowVS * 2;                // per wave
+  static constexpr int kVtBytes = D * kNarrowVS * 2 + (D / 32) * kNarrowShift;  // per wave
   static constexpr int kMergeBytes = NW * kDB * 16 * 64 * 4;        // partial O of the waves
   static constexpr int kLds = (kMergeBytes > NW * kVtBytes ? kMergeBytes : NW * kVtBytes) + NW * 32 * 8;
 };
@@ -447,8 +453,9 @@ __global__ __launch_bounds__((NarrowCfg<D, NW>::kThreads)) void attend_narrow_ke
       const u32x4 a = vr[2 * i], bq = vr[2 * i + 1];
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        vt32[(col * 8 + 2 * w) * (kNarrowVS / 2) + pair] = (a[w] & 0xFFFFu) | (bq[w] << 16);
-        vt32[(col * 8 + 2 * w + 1) * (kNarrowVS / 2) + pair] = (a[w] >> 16) | (bq[w] & 0xFFFF0000u);
+        const int word = (col * 8 + 2 * w) * (kNarrowVS / 2) + (col / 4) * (kNarrowShift / 4) + pair;
+        vt32[word] = (a[w] & 0xFFFFu) | (bq[w] << 16);
+        vt32[word + kNarrowVS / 2] = (a[w] >> 16) | (bq[w] & 0xFFFF0000u);
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -497,7 +504,8 @@ __global__ __launch_bounds__((NarrowCfg<D, NW>::kThreads)) void attend_narrow_ke
       for (int w = 0; w < 4; ++w) pf[w] = pack_bf16x2(s[8 * tp + 2 * w], s[8 * tp + 2 * w + 1]);
 #pragma unroll
       for (int db = 0; db < C::kDB; ++db) {
-        const char* rowp = reinterpret_cast<const char*>(vt32) + ((db * 32 + r) * kNarrowVS + 16 * tp + 4 * g) * 2;
+        const char* rowp =
+            reinterpret_cast<const char*>(vt32) + ((db * 32 + r) * kNarrowVS + 16 * tp + 4 * g) * 2 + db * kNarrowShift;
         const u32x2 lo = *reinterpret_cast<const u32x2*>(rowp);
         const u32x2 hi = *reinterpret_cast<const u32x2*>(rowp + 16);
         const u32x4 vf = {lo[0], lo[1], hi[0], hi[1]};
