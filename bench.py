@@ -39,7 +39,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
 # HBM bytes read + written by one launch of score pass 1 at the 32k prompt: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE,
 # each scaled by what it reads for a copy of known size (profiles/score_pass1_c4_hbm_traffic.md).  Other workloads: null.
-SCORE_PASS1_TRAFFIC_BYTES = {"C4": 141373.6 * 1024 * 2.0 + 1126.0 * 1024}
+SCORE_PASS1_TRAFFIC_BYTES = {"C4": 141376.0 * 1024 * 2.0 + 1126.0 * 1024}
 
 
 def workload(name: str) -> dict:
@@ -538,6 +538,9 @@ def main():
                     help="skip what runs after the timed region besides the full-cache attention: peaky logits, the "
                          "4k-prompt layer, the 8k-prompt stack, the batched ragged configuration, layer importance "
                          "and the probes")
+    ap.add_argument("--batched-only", action="store_true",
+                    help="run only the batched ragged configuration and print its block (for profiling that shape on "
+                         "its own; this is not the benchmark line)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="before the warm-up, copy 256 MiB device-to-device three times: a kernel of known traffic "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled")
@@ -550,10 +553,24 @@ def main():
     import torch
     from paper_2510_09309_amd import bench_binding as bb, binding as mk, synth
 
+    torch.cuda.set_device(0)
+
+    def calibration_copy():
+        src = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
+    if args.batched_only:
+        if args.calibration_copy:
+            calibration_copy()
+        print(json.dumps({"batched": batched_ragged(torch, mk, synth)}))
+        return
+
     cfg = workload(args.workload)
     H, d, P, n_m = cfg["H"], cfg["d"], cfg["P"], cfg["n_m"]
     N = P + n_m
-    torch.cuda.set_device(0)
     budgets_h = synth.config_budgets(args.workload, layer=1)      # the schedule's interior layers
     cap = int(budgets_h.sum())
     budgets = torch.from_numpy(budgets_h).cuda()
@@ -563,12 +580,7 @@ def main():
     stream = torch.cuda.current_stream()
 
     if args.calibration_copy:
-        src = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device="cuda").random_(0, 255)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        calibration_copy()
 
     # ---- the timed region: exactly --steps whole-path steps
     tr = timed_steps(torch, hev, path, budgets, args.steps, args.warmup, bb)

@@ -223,11 +223,15 @@ def prompt_preference(mass: np.ndarray, n_mask: int) -> np.ndarray:
 def head_budgets(P_h: np.ndarray, k_l: int, alpha: float = 0.1) -> np.ndarray:
     """k_{l,h} = floor(alpha*k_l + (1-alpha) * N_h * k_l * P_h / sum_j P_j)  (head budget formula).
 
-    k_l is the layer's per-head average budget, N_h the number of heads.
+    k_l is the layer's per-head average budget, N_h the number of heads.  The paper does not say what a
+    layer gets whose heads all have zero prompt preference (no prompt at all: the normalised preference
+    is 0/0).  Reading: with nothing to tell the heads apart the normalised preferences are equal, 1/N_h
+    each, which gives every head the average k_l.
     """
     P_h = _f64(P_h)
     n_h = P_h.shape[0]
-    p_hat = P_h / P_h.sum()
+    total = P_h.sum()
+    p_hat = P_h / total if total > 0.0 else np.full(n_h, 1.0 / n_h)
     return np.floor(alpha * k_l + (1.0 - alpha) * n_h * k_l * p_hat).astype(np.int64)
 
 

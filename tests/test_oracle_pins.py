@@ -415,6 +415,14 @@ def test_head_budgets_uniform_preference_and_bound():
     assert orc.head_budgets(np.array([0.125, 0.375]), 96, 0.25).tolist() == [60, 132]
 
 
+def test_head_budgets_without_any_prompt_preference_are_uniform():
+    # no prompt: every preference is zero and the normalised preference is 0/0; the reading taken is "equal shares",
+    # the limit of equal preferences eps -> 0: alpha*k_l + (1-alpha)*N_h*k_l/N_h = k_l for every head
+    assert orc.head_budgets(np.zeros(6), 100, 0.25).tolist() == [100] * 6
+    assert orc.head_budgets(np.full(6, 1e-300), 100, 0.25).tolist() == [100] * 6
+    assert orc.head_budgets(np.zeros(1), 7, 0.1).tolist() == [7]
+
+
 def test_layer_budgets_worked_case():
     # L = 4 layers, k_p = 1000, beta = 0.4: k_base = 100, k_imp = 600; importance B = {0.3, 0.3}, M = {0.2, 0.2}
     k = orc.layer_budgets(np.array([0.3, 0.2, 0.2, 0.3]), k_p=1000, beta=0.4)
