@@ -16,8 +16,9 @@
 // copy of the head's tiles in the index space, so a workgroup keeps one set of query fragments for a long run
 // of tiles, and the groups' column sums are added in a fixed order by a last small kernel.
 //
-// Tiling: one workgroup = 4 waves; each wave keeps 64 queries as MFMA operands in registers; K tiles
-// stream through a padded, double-buffered LDS tile shared by the four waves.  Pass 1 puts keys on the
+// Tiling: a workgroup holds the 256 voting rows of its query group as MFMA operands in registers - four waves
+// of 64 queries, except bf16 pass 1, which runs eight waves of 32 (see ScoreCfg) - and K tiles stream through a
+// padded, double-buffered LDS tile shared by its waves.  Pass 1 puts keys on the
 // MFMA row axis so that a lane owns one query and the softmax statistics never leave the lane; pass 2
 // puts queries on the row axis so that the sum over queries is in-lane adds plus one cross-lane exchange.
 #include <type_traits>
