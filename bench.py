@@ -117,6 +117,7 @@ class Path:
 
     def __init__(self, torch, mk, cfg, layers, capacity):
         self.mk, self.cfg, self.layers = mk, cfg, layers
+        self.row_lse = None            # per resident layer: natural-log row normalisers, if scoring is to use them
         H, d, P, n_m = cfg["H"], cfg["d"], cfg["P"], cfg["n_m"]
         self.desc = mk.Desc(B=1, H=H, d=d, dtype=mk.MASKKV_BF16, n_resp=n_m, P_max=P)
         self.resp = [(mk.tensor_view(K, seq_start=[P]), mk.tensor_view(V, seq_start=[P])) for (_, K, V) in layers]
@@ -139,7 +140,10 @@ class Path:
 
     def score(self, i, stream, marks=None, bb=None):
         Q, K, _ = self.layers[i % len(self.layers)]
-        if marks is None:
+        if self.row_lse is not None:   # the second scoring pass alone, from given row normalisers
+            self.mk.maskkv_score_given_lse(self.desc, Q, K, 0.0, self.row_lse[i % len(self.layers)], self.scores,
+                                           self.stride, self.mass, self.ws_score, stream)
+        elif marks is None:
             self.mk.maskkv_score(self.desc, Q, K, 0.0, self.scores, self.stride, self.mass, self.ws_score, stream)
         else:   # the same launches, with events recorded around the passes
             bb.maskkv_bench_score_marked(self.desc, Q, K, 0.0, self.scores, self.stride, self.mass, self.ws_score,
@@ -191,8 +195,10 @@ def timed_steps(torch, hev, path, budgets, steps, warmup, bb):
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / steps
     span = lambda a, b: [hev.elapsed_ms(e[a], e[b]) for e in ev]
-    out = {"wall_ms_per_step": wall_ms, "score": span(0, 3), "pass1": span(1, 2), "select": span(3, 4),
-           "compact": span(4, 5), "attend": span(5, 6), "evict": span(0, 5), "step": span(0, 6)}
+    out = {"wall_ms_per_step": wall_ms, "score": span(0, 3), "select": span(3, 4), "compact": span(4, 5),
+           "attend": span(5, 6), "evict": span(0, 5), "step": span(0, 6)}
+    if path.row_lse is None:   # (the marks around pass 1 are only recorded by the two-pass call)
+        out["pass1"] = span(1, 2)
     for e in ev:
         for x in e:
             hev.destroy(x)
@@ -645,6 +651,22 @@ def main():
     }
 
     if not args.no_extras:
+        # ---- scoring when the rows' normalisers come from the model's own first-step attention over the full sequence
+        # (maskkv_attend_full returns them): the second scoring pass alone.  Not the headline: `value` above is the
+        # stand-alone two-pass call.
+        path.row_lse = []
+        for (Q, K, V) in layers:
+            lse = torch.empty(H * n_m, dtype=torch.float32, device="cuda")
+            mk.maskkv_attend_full(path.desc, Q, K, V, 0.0, path.Of, lse, path.ws_full, stream)
+            path.row_lse.append(lse)
+        tg = timed_steps(torch, hev, path, budgets, 32, 4, bb)
+        path.row_lse = None
+        out["given_row_lse"] = {
+            "what": "the same step with maskkv_score_given_lse (row normalisers from maskkv_attend_full of the same "
+                    "queries) in place of maskkv_score: 32 timed steps, HIP events as in the timed region",
+            "ms_per_step": tg["wall_ms_per_step"],
+            "timed_region_ms": {k: stats(tg[k]) for k in ("score", "select", "compact", "attend", "evict")},
+            "prompt_tokens_scored_evicted_per_s": P / (float(np.mean(tg["evict"])) * 1e-3)}
         # ---- the same MFMA calls on peaky logits (components 9.5 x wider: softmax rows concentrate on few keys, so
         # the lazily raised running references of scoring and attention leave their cheapest branch)
         peaky = [device_layer(torch, cfg, 100 + l, sigma=9.5) for l in range(2)]

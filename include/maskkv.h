@@ -133,6 +133,21 @@ int maskkv_score(const maskkv_desc* desc, const maskkv_tensor* Q_mask, const mas
                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Mask-Voting when the softmax normaliser of every voting row is already known.  At the initial inference step
+ * (the step whose mask queries vote, Stage 1) the model's own attention over the un-evicted sequence forms the
+ * same logits over the same keys, and a flash-style attention call returns each row's log-sum-exp: given those,
+ * the scores need one sweep over the keys instead of two.
+ *   row_lse[(b*H + h)*g*n_query + r] = log sum_j exp(q_r . k_j * scale)   (natural log, all N_b keys)
+ * for voting row r of key/value head h (rows numbered as the rows of Q_mask: query head first, then query) - the
+ * layout in which maskkv_attend_full writes `lse` when it is called with the same queries (n_query = n_resp) and
+ * the same scale.  scores and prompt_mass as for maskkv_score; they equal its results up to the rounding of the
+ * normalisers.  workspace: maskkv_score_workspace_bytes (only the part for more than 256 voting rows is used).
+ */
+int maskkv_score_given_lse(const maskkv_desc* desc, const maskkv_tensor* Q_mask, const maskkv_tensor* K_full,
+                           float scale, const float* row_lse, float* scores, int64_t score_stride,
+                           float* prompt_mass, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * maskkv_score for callers that cannot allocate device memory or carry a workspace: code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc.  Same arguments and same result as maskkv_score, but the
  * scratch between the passes lives in an array of MASKKV_STATIC_SCRATCH_BYTES that is part of the library image

@@ -24,7 +24,7 @@ MAX_BATCH = 64
 
 SYMBOLS = [
     "maskkv_version", "maskkv_strerror", "maskkv_last_error",
-    "maskkv_score_workspace_bytes", "maskkv_score", "maskkv_score_static",
+    "maskkv_score_workspace_bytes", "maskkv_score", "maskkv_score_given_lse", "maskkv_score_static",
     "maskkv_select_workspace_bytes", "maskkv_select",
     "maskkv_compact",
     "maskkv_attend_workspace_bytes", "maskkv_attend", "maskkv_attend_full",
@@ -163,6 +163,17 @@ def maskkv_score(desc: Desc, Q_mask, K_full, scale: float, scores: torch.Tensor,
     wp, wn = _ws(workspace)
     _check(_lib.maskkv_score(ct.byref(desc.c()), ct.byref(q), ct.byref(k), ct.c_float(scale), _ptr(scores),
                              ct.c_int64(score_stride), _ptr(prompt_mass), wp, wn, _stream(stream)), "maskkv_score")
+
+
+def maskkv_score_given_lse(desc: Desc, Q_mask, K_full, scale: float, row_lse: torch.Tensor, scores: torch.Tensor,
+                           score_stride: int, prompt_mass: Optional[torch.Tensor], workspace: Optional[torch.Tensor],
+                           stream=None) -> None:
+    """maskkv_score from the rows' natural-log softmax normalisers (as maskkv_attend_full returns them)."""
+    q, k = _as_view(Q_mask), _as_view(K_full)
+    wp, wn = _ws(workspace)
+    _check(_lib.maskkv_score_given_lse(ct.byref(desc.c()), ct.byref(q), ct.byref(k), ct.c_float(scale), _ptr(row_lse),
+                                       _ptr(scores), ct.c_int64(score_stride), _ptr(prompt_mass), wp, wn,
+                                       _stream(stream)), "maskkv_score_given_lse")
 
 
 def maskkv_score_static(desc: Desc, Q_mask, K_full, scale: float, scores: torch.Tensor, score_stride: int,

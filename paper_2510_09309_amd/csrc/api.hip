@@ -221,6 +221,24 @@ int maskkv_score(const maskkv_desc* desc, const maskkv_tensor* Q_mask, const mas
                      stream, nullptr);
 }
 
+int maskkv_score_given_lse(const maskkv_desc* desc, const maskkv_tensor* Q_mask, const maskkv_tensor* K_full,
+                           float scale, const float* row_lse, float* scores, int64_t score_stride,
+                           float* prompt_mass, void* workspace, size_t workspace_bytes, void* stream) {
+  Lens lens;
+  View q, k;
+  if (int e = check_desc(desc, &lens)) return e;
+  if (int e = make_view(desc, Q_mask, "Q_mask", &q)) return e;
+  if (int e = make_view(desc, K_full, "K_full", &k)) return e;
+  if (!row_lse || !scores || score_stride < desc->P_max) {
+    set_error("row_lse or scores is NULL, or score_stride %lld < P_max %d", (long long)score_stride, desc->P_max);
+    return MASKKV_EINVAL;
+  }
+  if (int e = check_workspace("score_given_lse", workspace, workspace_bytes, score_workspace_bytes(desc, lens)))
+    return e;
+  return launch_score(desc, q, k, lens, pick_scale(desc, scale), scores, score_stride, prompt_mass, workspace,
+                      reinterpret_cast<hipStream_t>(stream), nullptr, row_lse);
+}
+
 int maskkv_score_static(const maskkv_desc* desc, const maskkv_tensor* Q_mask, const maskkv_tensor* K_full, float scale,
                         float* scores, int64_t score_stride, float* prompt_mass, void* stream) {
   Lens lens;

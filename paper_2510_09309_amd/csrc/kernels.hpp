@@ -9,7 +9,7 @@ namespace maskkv {
 size_t score_workspace_bytes(const maskkv_desc* d, const Lens& lens);
 int launch_score(const maskkv_desc* d, const View& Q, const View& K, const Lens& lens, float scale, float* scores,
                  int64_t score_stride, float* prompt_mass, void* workspace, hipStream_t stream,
-                 void* const* events);
+                 void* const* events, const float* row_lse = nullptr);
 
 // select.hip
 size_t select_workspace_bytes(const maskkv_desc* d);

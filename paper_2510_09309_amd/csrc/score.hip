@@ -80,6 +80,7 @@ struct ScoreParams {
   float c;            // scale * log2(e)
   float2* stats;      // [B*H][parts_p + parts_r][n_query] (reference, sum) in the base-2 domain
   float* lse2;        // [B*H][n_query]
+  const float* row_lse;  // [B*H][n_query] natural-log normalisers given by the caller (then pass 1 is not run), or null
   float* scores;      // [B*H][score_stride]
   int64_t score_stride;
   float* group_sums;  // [B*H][nqg][group_stride] column sums per query group (more than one group only)
@@ -182,7 +183,9 @@ __global__ __launch_bounds__((ScoreCfg<T, D, PASS>::kThreads), (ScoreCfg<T, D, P
           __syncthreads();
           const int q = qg + (int)threadIdx.x;
           if ((int)threadIdx.x < kQPerGroup)
-            nlse[threadIdx.x] = q < prm.n_query ? -prm.lse2[(int64_t)bh * prm.n_query + q] : -INFINITY;
+            nlse[threadIdx.x] = q >= prm.n_query ? -INFINITY
+                                : prm.row_lse    ? -prm.row_lse[(int64_t)bh * prm.n_query + q] * kLog2e
+                                                 : -prm.lse2[(int64_t)bh * prm.n_query + q];
           __syncthreads();
 #pragma unroll
           for (int blk = 0; blk < C::kNQ; ++blk)
@@ -402,6 +405,36 @@ __global__ __launch_bounds__(256) void score_group_sum_kernel(const ScoreParams 
   prm.scores[(int64_t)bh * prm.score_stride + j] = v;
 }
 
+// Prompt mass as the sum of a head's scores (the column sums of the prompt columns add up to the prompt's share of
+// the voting rows' attention), for calls that do not run pass 1: one 1024-thread workgroup per (b, h), eight
+// independent loads in flight per thread, fixed summation order.
+constexpr int kMassThreads = 1024;
+
+__global__ __launch_bounds__(kMassThreads) void score_mass_kernel(const ScoreParams prm) {
+  __shared__ float red[kMassThreads];
+  const int bh = blockIdx.x;
+  const int P = prm.lens.P[bh / prm.H];
+  const float* row = prm.scores + (int64_t)bh * prm.score_stride;
+  float acc = 0.f;
+  for (int j0 = threadIdx.x; j0 < P; j0 += 8 * kMassThreads) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int j = j0 + u * kMassThreads;
+      v[u] = j < P ? row[j] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += v[u];
+  }
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int s = kMassThreads / 2; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) prm.prompt_mass[bh] = red[0];
+}
+
 int tile_keys(const maskkv_desc*) { return 64; }  // every configuration uses 64-key tiles
 
 int query_groups(const maskkv_desc* d) {
@@ -477,12 +510,14 @@ int launch_pass(const ScoreParams& prm, hipStream_t stream) {
 template <typename T, int D>
 int launch_score_t(ScoreParams& prm, const TileMap& map2, hipStream_t stream, void* const* events) {
   if (int e = mark(events, 0, stream)) return e;
-  prm.map = prm.map1;
-  if (int e = launch_pass<T, D, 1>(prm, stream)) return e;
-  if (int e = mark(events, 1, stream)) return e;
-  hipLaunchKernelGGL(score_merge_kernel, dim3(prm.B * prm.H), dim3(256), 0, stream, prm);
-  if (int e = check_launch("score merge")) return e;
-  if (int e = mark(events, 2, stream)) return e;
+  if (!prm.row_lse) {
+    prm.map = prm.map1;
+    if (int e = launch_pass<T, D, 1>(prm, stream)) return e;
+    if (int e = mark(events, 1, stream)) return e;
+    hipLaunchKernelGGL(score_merge_kernel, dim3(prm.B * prm.H), dim3(256), 0, stream, prm);
+    if (int e = check_launch("score merge")) return e;
+    if (int e = mark(events, 2, stream)) return e;
+  }
   if (map2.T > 0) {
     prm.map = map2;
     if (int e = launch_pass<T, D, 2>(prm, stream)) return e;
@@ -491,6 +526,10 @@ int launch_score_t(ScoreParams& prm, const TileMap& map2, hipStream_t stream, vo
       hipLaunchKernelGGL(score_group_sum_kernel, grid, dim3(256), 0, stream, prm, map2.nqg);
       if (int e = check_launch("score (group sums)")) return e;
     }
+  }
+  if (prm.row_lse && prm.prompt_mass) {
+    hipLaunchKernelGGL(score_mass_kernel, dim3(prm.B * prm.H), dim3(kMassThreads), 0, stream, prm);
+    if (int e = check_launch("score (prompt mass)")) return e;
   }
   return mark(events, 3, stream);
 }
@@ -512,8 +551,9 @@ size_t score_workspace_bytes(const maskkv_desc* d, const Lens& lens) {
 
 int launch_score(const maskkv_desc* d, const View& Q, const View& K, const Lens& lens, float scale, float* scores,
                  int64_t score_stride, float* prompt_mass, void* workspace, hipStream_t stream,
-                 void* const* events) {
+                 void* const* events, const float* row_lse) {
   ScoreParams prm;
+  prm.row_lse = row_lse;
   prm.Q = Q;
   prm.K = K;
   prm.lens = lens;

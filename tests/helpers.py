@@ -77,6 +77,17 @@ def gpu_score(batch: Batch, scale: float = 0.0):
     return scores, mass
 
 
+def gpu_score_given_lse(batch: Batch, row_lse: torch.Tensor, scale: float = 0.0):
+    """Scores and prompt mass from given natural-log row normalisers [B*H*n_m]; padding stays NaN."""
+    m = mk()
+    scores = torch.full((batch.B * batch.H, batch.P_max), float("nan"), dtype=torch.float32, device="cuda")
+    mass = torch.full((batch.B * batch.H,), float("nan"), dtype=torch.float32, device="cuda")
+    ws = workspace(m.maskkv_score_workspace_bytes(batch.desc))
+    m.maskkv_score_given_lse(batch.desc, batch.Q, batch.K, scale, row_lse, scores, batch.P_max, mass, ws)
+    torch.cuda.synchronize()
+    return scores, mass
+
+
 def gpu_select(batch: Batch, scores: torch.Tensor, budgets: np.ndarray, window: int, mode: int = 0, capacity=None):
     m = mk()
     BH = batch.B * batch.H

@@ -128,6 +128,13 @@ def test_bad_call_arguments_are_rejected_before_launch(mk):
     assert call_score(good, good, 128, None, 0) == 4            # no workspace
     assert call_score(good, good, 128, f, 16) == 4              # too small
     assert call_score(good, good, 128, ct.c_void_p(fake + 8), 1 << 20) == 4  # misaligned workspace
+    given = lambda lse, stride, ws, wsn: lib.maskkv_score_given_lse(
+        ct.byref(desc), ct.byref(good), ct.byref(good), ct.c_float(0), lse, f, ct.c_int64(stride), None, ws,
+        ct.c_size_t(wsn), None)
+    assert given(None, 128, f, 1 << 20) == 1                    # no row normalisers
+    assert b"row_lse" in lib.maskkv_last_error()
+    assert given(f, 64, f, 1 << 20) == 1                        # score_stride < P_max
+    assert given(f, 128, None, 0) == 4                          # no workspace
     sel = lambda window, mode, cap: lib.maskkv_select(
         ct.byref(desc), f, ct.c_int64(128), ct.c_int(window), ct.c_int(mode), f, None, f, f, ct.c_int64(cap), None,
         ct.c_size_t(0), None)
