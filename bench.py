@@ -415,6 +415,8 @@ def measured_peaks(torch, bb):
     mfma = rate(lambda: bb.maskkv_bench_probe(0, 20000, None, out, 512), 3)      # two waves per SIMD
     data2 = rate(lambda: bb.maskkv_bench_probe(5, 5000, operands, out, 512), 3)  # two waves per SIMD
     data1 = rate(lambda: bb.maskkv_bench_probe(5, 5000, operands, out, 256), 3)  # one wave per SIMD
+    pipe2 = rate(lambda: bb.maskkv_bench_probe(6, 5000, operands, out, 512), 3)  # two waves per SIMD, as score pass 2
+    pipe4 = rate(lambda: bb.maskkv_bench_probe(6, 5000, operands, out, 1024), 3) # four waves per SIMD
     exps = rate(lambda: bb.maskkv_bench_probe(1, 20000, None, out, 2048), 3)     # eight waves per SIMD
     mix = rate(lambda: bb.maskkv_bench_probe(4, 5000, None, out, 512), 3)        # two waves per SIMD, as score pass 2
     copy = rate(lambda: bb.maskkv_bench_probe(2, 0, src, dst, 2048), 5)
@@ -423,10 +425,13 @@ def measured_peaks(torch, bb):
             "mfma_bf16_tflops_gaussian_operands": {"two_waves_per_simd": data2 / 1e12, "one_wave_per_simd": data1 / 1e12},
             "v_exp_f32_per_s": exps, "stream_copy_gbs": copy / 1e9, "stream_read_gbs": read / 1e9,
             "score_instruction_mix_tflops": mix / 1e12,
+            "score_pipeline_on_gaussian_operands_tflops": {"two_waves_per_simd": pipe2 / 1e12,
+                                                           "four_waves_per_simd": pipe4 / 1e12},
             "how": "maskkv_bench_probe: register-only v_mfma_f32_32x32x16_bf16 loops (constant operands; Gaussian bf16 "
                    "operands read once from memory into registers), v_exp_f32 loop on 2048 workgroups, 1 GiB copy "
                    "(read + written bytes), 1 GiB read; instruction mix = 16 MFMAs + 32 x (fma, exp, add) per lane per "
-                   "iteration on 512 workgroups, no memory traffic"}
+                   "iteration on 512 workgroups, no memory traffic; pipeline = the same sixteen MFMAs on Gaussian operands "
+                   "into one accumulator pair while the exponentials consume the pair formed one iteration earlier"}
 
 
 def layer_importance_rate(torch, mk, n_tokens, hidden=4096):
@@ -708,6 +713,8 @@ def main():
             "mfma_time_us_on_gaussian_operands": flop_qk_all / (gauss2 * 1e12) * 1e6,
             "exp_time_us": n_exp / peaks["v_exp_f32_per_s"] * 1e6,
             "instruction_mix_time_us": flop_qk_all / (peaks["score_instruction_mix_tflops"] * 1e12) * 1e6,
+            "pipeline_on_gaussian_operands_time_us": flop_qk_all / (
+                peaks["score_pipeline_on_gaussian_operands_tflops"]["two_waves_per_simd"] * 1e12) * 1e6,
             "k_stream_time_us": bytes_k / (peaks["stream_read_gbs"] * 1e9) * 1e6,
             "measured_us": pass1_ms * 1e3}
         out["measured_peaks"] = peaks

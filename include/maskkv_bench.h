@@ -32,8 +32,12 @@ const char* maskkv_bench_last_error(void);
  *              from zero, with operands from 24 register sets loaded from src (24 KiB: fill it with the bit
  *              patterns a kernel really sees; the matrix pipe's sustained rate depends on them);
  *                                                                                *work = floating-point operations
+ *   which = 6  the scoring kernels' form-and-reduce pipeline on data, from registers: per iteration every wave
+ *              forms two 32x32 logits blocks (16 MFMAs, operands as for which = 5) into one accumulator pair and
+ *              takes the exponentials of the pair formed one iteration earlier (32 x (multiply, v_exp_f32, add)
+ *              per lane); iterations run in pairs;                *work = floating-point operations of the MFMAs
  * dst: DEVICE of dst_bytes bytes; for which != 2 it receives groups*256 32-bit words, for which = 2 it is the copy
- * target.  src: DEVICE, 16-byte aligned; `bytes` a multiple of 16 (which = 2, 3) or at least 24576 (which = 5);
+ * target.  src: DEVICE, 16-byte aligned; `bytes` a multiple of 16 (which = 2, 3) or at least 24576 (which = 5, 6);
  * ignored otherwise.  work: HOST double, may be NULL.  groups: 256-thread workgroups launched, 1..2^20.
  * MASKKV_EINVAL on any violation.
  */

@@ -102,6 +102,49 @@ __global__ __launch_bounds__(kProbeThreads) void probe_mix_kernel(int iters, flo
   out[(int64_t)blockIdx.x * kProbeThreads + threadIdx.x] = s;
 }
 
+// The scoring kernels' form-and-reduce pipeline from registers only, on data: per iteration every wave forms the
+// logits of two 32x32 blocks (16 MFMAs at head_dim 128, two chains of eight that start from zero, operands from the
+// 24 register sets loaded from `src`) into one accumulator pair while it takes the exponentials of the pair formed
+// one iteration earlier (32 x (multiply, v_exp_f32, add) per lane), in one basic block, as the kernels do.  Unlike
+// probe_mix_kernel the vector work consumes the matrix pipe's results and the operands toggle like real data.
+__global__ __launch_bounds__(kProbeThreads) void probe_pipeline_kernel(int iters, const u32x4* src, float* out) {
+  u32x4 ka[2][8], qf[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    ka[0][i] = src[(threadIdx.x & 63) + 64 * i];
+    ka[1][i] = src[(threadIdx.x & 63) + 64 * (8 + i)];
+    qf[i] = src[(threadIdx.x & 63) + 64 * (16 + i)];
+  }
+  f32x16 accA[2] = {f32x16{}, f32x16{}}, accB[2] = {f32x16{}, f32x16{}};
+  const float c = 0.127f;
+  float sum = 0.f;
+  // `flip` pairs the operand sets differently in the two stages of a loop trip and one operand word changes from
+  // trip to trip, so that no block is the same computation as another one.
+  auto stage = [&](f32x16 (&next)[2], f32x16 (&cur)[2], int flip) {
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk) next[blk] = f32x16{};
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+      for (int blk = 0; blk < 2; ++blk) mfma_step<bf16_t>(ka[blk ^ flip][ks], qf[(ks + flip) & 7], next[blk]);
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sum += fast_exp2(cur[blk][i] * c);
+  };
+  for (int it = 0; it < iters; it += 2) {
+    qf[0][0] ^= 0x00010000u;  // the lowest mantissa bit of one bf16 operand element
+    stage(accB, accA, 0);
+    stage(accA, accB, 1);
+  }
+  float s = sum;
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += accA[u][i] + accB[u][i];
+  out[(int64_t)blockIdx.x * kProbeThreads + threadIdx.x] = s;
+}
+
 // Every lane runs iters * kExpChains v_exp_f32 (x <- 2^-|x|: the sign and magnitude modifiers are free, the
 // values stay in (0, 1]).
 __global__ __launch_bounds__(kProbeThreads) void probe_exp_kernel(int iters, float* out) {
@@ -178,13 +221,13 @@ const char* maskkv_bench_last_error(void) { return g_bench_err; }
 int maskkv_bench_probe(int which, int32_t iters, const void* src, void* dst, int64_t bytes, int64_t dst_bytes,
                        int32_t groups, void* stream_, double* work) {
   hipStream_t stream = reinterpret_cast<hipStream_t>(stream_);
-  if (which < 0 || which > 5 || !dst || groups < 1 || groups > (1 << 20))
-    return fail("probe: which outside 0..5, dst NULL or groups outside 1..2^20");
+  if (which < 0 || which > 6 || !dst || groups < 1 || groups > (1 << 20))
+    return fail("probe: which outside 0..6, dst NULL or groups outside 1..2^20");
   if (which != 2 && dst_bytes < (int64_t)groups * kProbeThreads * 4)
     return fail("probe: dst is smaller than groups*256 words");
-  const bool arithmetic = which == 0 || which == 1 || which == 4 || which == 5;
+  const bool arithmetic = which == 0 || which == 1 || which >= 4;
   if (arithmetic && iters < 1) return fail("probe: iters < 1");
-  if (which == 5 && (!src || ((uintptr_t)src & 15) || bytes < 64 * 24 * 16))
+  if (which >= 5 && (!src || ((uintptr_t)src & 15) || bytes < 64 * 24 * 16))
     return fail("probe: the data-fed matrix probe reads 24 KiB of operands from a 16-byte aligned src");
   if ((which == 2 || which == 3) &&
       (!src || bytes < 16 || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15) ||
@@ -197,6 +240,7 @@ int maskkv_bench_probe(int which, int32_t iters, const void* src, void* dst, int
       case 1: *work = (double)groups * kProbeThreads * kExpChains * iters; break;
       case 2: *work = 2.0 * (double)bytes; break;
       case 3: *work = (double)bytes; break;
+      case 6: *work = waves * 16.0 * ((iters + 1) / 2 * 2) * 32768.0; break;  // (iterations come in pairs)
       default: *work = waves * 16.0 * iters * 32768.0; break;  // 4, 5: sixteen MFMAs per iteration
     }
   }
@@ -219,10 +263,14 @@ int maskkv_bench_probe(int which, int32_t iters, const void* src, void* dst, int
     case 4:
       hipLaunchKernelGGL(probe_mix_kernel, dim3(groups), dim3(kProbeThreads), 0, stream, iters, out);
       return launched("probe (mix)");
-    default:
+    case 5:
       hipLaunchKernelGGL(probe_mfma_data_kernel, dim3(groups), dim3(kProbeThreads), 0, stream, iters,
                          reinterpret_cast<const u32x4*>(src), out);
       return launched("probe (mfma on data)");
+    default:
+      hipLaunchKernelGGL(probe_pipeline_kernel, dim3(groups), dim3(kProbeThreads), 0, stream, iters,
+                         reinterpret_cast<const u32x4*>(src), out);
+      return launched("probe (form-and-reduce pipeline on data)");
   }
 }
 

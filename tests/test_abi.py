@@ -51,7 +51,8 @@ def test_bench_library_exports_its_header_and_rejects_bad_probes():
     probe = lambda which, iters, src, nbytes, dst_bytes, groups: lib.maskkv_bench_probe(
         ct.c_int(which), ct.c_int32(iters), src, f, ct.c_int64(nbytes), ct.c_int64(dst_bytes), ct.c_int32(groups), None,
         None)
-    assert probe(6, 10, None, 0, 1 << 20, 8) == 1              # unknown probe
+    assert probe(7, 10, None, 0, 1 << 20, 8) == 1              # unknown probe
+    assert probe(6, 10, None, 0, 1 << 20, 8) == 1              # pipeline probe: operands missing
     assert probe(4, 0, None, 0, 1 << 20, 8) == 1               # no iterations
     assert probe(0, 0, None, 0, 1 << 20, 8) == 1               # no iterations
     assert probe(0, 10, None, 0, 8 * 256 * 4 - 4, 8) == 1      # result buffer too small

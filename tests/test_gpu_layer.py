@@ -84,6 +84,7 @@ def test_measurement_probes_run_and_the_copy_is_exact():
     operands = (torch.randn(64 * 24 * 8, device="cuda") / 11.3).to(torch.bfloat16)   # 24 KiB of Gaussian bf16
     out.fill_(float("nan"))
     assert bb.maskkv_bench_probe(5, 10, operands, out, 8) == 8 * 4 * 16 * 10 * 32768.0
+    assert bb.maskkv_bench_probe(6, 9, operands, out, 8) == 8 * 4 * 16 * 10 * 32768.0      # iterations run in pairs
     torch.cuda.synchronize()
     assert bool(torch.isfinite(out).all())
     src = torch.arange(100003 * 4, dtype=torch.int32, device="cuda")               # a ragged number of 16-byte pieces
