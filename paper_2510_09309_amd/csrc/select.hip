@@ -20,6 +20,10 @@
 // in order with ballot/popcount prefix sums, each wave walking one contiguous slice.
 #include "kernels.hpp"
 
+#ifndef SEL_SLACK
+#define SEL_SLACK 64
+#endif
+
 namespace maskkv {
 
 namespace {
@@ -31,6 +35,7 @@ constexpr int kSelLdsCap = 32768;  // final stage: keys kept in LDS (128 KB) nex
 constexpr int kBins = 2048;
 constexpr int kBinsPerLane = kBins / 64;
 constexpr int kHistWords = kBins + kBins / kBinsPerLane;  // one pad word per 32 bins: conflict-free lane walks
+constexpr int kChunkSlack = SEL_SLACK;  // a chunk stops refining its threshold at this many keys in the bin
 constexpr int kMaxChunks = 1024;   // chunk offsets of a head are kept in LDS: prompts of up to 4 Mi tokens
 
 struct SelectParams {
@@ -52,6 +57,7 @@ struct SelectParams {
 struct SelState {
   uint32_t lo, hi;  // current key range
   int krem;         // rank wanted inside it
+  int binpop;       // keys inside it
 };
 
 __device__ __forceinline__ uint32_t order_key(float v) {
@@ -125,14 +131,16 @@ __device__ __forceinline__ void pick_bin(int* hist, const Round& rd, uint32_t hi
   const int incl = wave_incl_scan(s, lane);
   int above = incl - s;
   if (incl >= krem && above < krem) {  // exactly one lane owns the bin
-    int bsel = -1;
+    int bsel = -1, pop = 0;
 #pragma unroll
     for (int j = 0; j < kBinsPerLane; ++j) {
       if (bsel < 0) {
-        if (above + h[j] >= krem)
+        if (above + h[j] >= krem) {
           bsel = lane * kBinsPerLane + j;
-        else
+          pop = h[j];
+        } else {
           above += h[j];
+        }
       }
     }
     const uint32_t nlo = rd.lo + ((uint32_t)(rd.nb - 1 - bsel) << rd.shift);
@@ -140,6 +148,7 @@ __device__ __forceinline__ void pick_bin(int* hist, const Round& rd, uint32_t hi
     st->lo = nlo;
     st->hi = (uint32_t)min((uint64_t)hi, (uint64_t)nlo + span);
     st->krem = krem - above;
+    st->binpop = pop;
   }
 }
 
@@ -243,10 +252,12 @@ __global__ __launch_bounds__(kSelThreads) void select_chunk_kernel(const SelectP
     lo = min(lo, wmin[w]);
     hi = max(hi, wmax[w]);
   }
-  // ---- the chunk's kc-th largest key, exactly: range refinement over the keys in registers
+  // ---- a lower bound of the chunk's kc-th largest key: range refinement over the keys in registers, until the
+  // bin that holds it has few keys left (every key of that bin becomes a candidate, so the bound need not be tight;
+  // the final stage finds the head's threshold exactly)
   if (kc < n) {
-    int krem = kc;
-    for (int round = 0; round < 4 && lo != hi; ++round) {
+    int krem = kc, binpop = n;
+    for (int round = 0; round < 4 && lo != hi && binpop > kChunkSlack; ++round) {
       const Round rd(lo, hi);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -259,6 +270,7 @@ __global__ __launch_bounds__(kSelThreads) void select_chunk_kernel(const SelectP
       lo = st.lo;
       hi = st.hi;
       krem = st.krem;
+      binpop = st.binpop;
     }
   }
   const uint32_t t0 = lo;  // kc >= n: the smallest key, everything is a candidate
