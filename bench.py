@@ -429,6 +429,21 @@ def measured_peaks(torch, bb):
     pipe4 = rate(lambda: bb.maskkv_bench_probe(6, 5000, operands, out, 1024), 3) # four waves per SIMD
     exps = rate(lambda: bb.maskkv_bench_probe(1, 20000, None, out, 2048), 3)     # eight waves per SIMD
     mix = rate(lambda: bb.maskkv_bench_probe(4, 5000, None, out, 512), 3)        # two waves per SIMD, as score pass 2
+
+    def ns_per_iteration(which, iters=5000):   # 256 eight-wave workgroups: one matrix wave + one vector wave per SIMD
+        bb.maskkv_bench_probe(which, iters, operands, out, 256)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(3):
+            bb.maskkv_bench_probe(which, iters, operands, out, 256)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e6 / (3 * iters)
+    split = {"both_halves": ns_per_iteration(7), "matrix_waves_alone": ns_per_iteration(8),
+             "vector_waves_alone": ns_per_iteration(9)}
+    split["both_over_the_longer_alone"] = split["both_halves"] / max(split["matrix_waves_alone"],
+                                                                       split["vector_waves_alone"])
     copy = rate(lambda: bb.maskkv_bench_probe(2, 0, src, dst, 2048), 5)
     read = rate(lambda: bb.maskkv_bench_probe(3, 0, src, out, 2048), 5)
     return {"mfma_bf16_tflops_constant_operands": mfma / 1e12,
@@ -437,11 +452,14 @@ def measured_peaks(torch, bb):
             "score_instruction_mix_tflops": mix / 1e12,
             "score_pipeline_on_gaussian_operands_tflops": {"two_waves_per_simd": pipe2 / 1e12,
                                                            "four_waves_per_simd": pipe4 / 1e12},
+            "matrix_and_vector_waves_on_one_simd_ns_per_iteration": split,
             "how": "maskkv_bench_probe: register-only v_mfma_f32_32x32x16_bf16 loops (constant operands; Gaussian bf16 "
                    "operands read once from memory into registers), v_exp_f32 loop on 2048 workgroups, 1 GiB copy "
                    "(read + written bytes), 1 GiB read; instruction mix = 16 MFMAs + 32 x (fma, exp, add) per lane per "
                    "iteration on 512 workgroups, no memory traffic; pipeline = the same sixteen MFMAs on Gaussian operands "
-                   "into one accumulator pair while the exponentials consume the pair formed one iteration earlier"}
+                   "into one accumulator pair while the exponentials consume the pair formed one iteration earlier; matrix and "
+                   "vector waves = 256 eight-wave workgroups whose waves 0-3 issue those sixteen MFMAs and whose waves 4-7 "
+                   "issue 32 x (multiply, exp, add) per iteration (waves w and w+4 share a SIMD), together and each half alone"}
 
 
 def layer_importance_rate(torch, mk, n_tokens, hidden=4096):

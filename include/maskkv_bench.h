@@ -36,10 +36,16 @@ const char* maskkv_bench_last_error(void);
  *              forms two 32x32 logits blocks (16 MFMAs, operands as for which = 5) into one accumulator pair and
  *              takes the exponentials of the pair formed one iteration earlier (32 x (multiply, v_exp_f32, add)
  *              per lane); iterations run in pairs;                *work = floating-point operations of the MFMAs
- * dst: DEVICE of dst_bytes bytes; for which != 2 it receives groups*256 32-bit words, for which = 2 it is the copy
- * target.  src: DEVICE, 16-byte aligned; `bytes` a multiple of 16 (which = 2, 3) or at least 24576 (which = 5, 6);
- * ignored otherwise.  work: HOST double, may be NULL.  groups: 256-thread workgroups launched, 1..2^20.
- * MASKKV_EINVAL on any violation.
+ *   which = 7  do the two pipes of a SIMD serve different waves at the same time?  512-thread workgroups (waves w
+ *              and w + 4 share a SIMD): per iteration waves 0-3 issue the sixteen MFMAs of which = 5, waves 4-7
+ *              32 x (multiply, v_exp_f32, add) per lane; iterations run in pairs;
+ *                                                                 *work = floating-point operations of the MFMAs
+ *   which = 8  as 7, the matrix waves alone (waves 4-7 exit at once);                                 *work as for 7
+ *   which = 9  as 7, the vector waves alone (waves 0-3 exit at once);                           *work = exponentials
+ * dst: DEVICE of dst_bytes bytes; for which != 2 it receives one 32-bit word per launched thread, for which = 2 it
+ * is the copy target.  src: DEVICE, 16-byte aligned; `bytes` a multiple of 16 (which = 2, 3) or at least 24576
+ * (which = 5 ... 9); ignored otherwise.  work: HOST double, may be NULL.  groups: workgroups launched (256 threads
+ * each, 512 for which >= 7), 1..2^20.  MASKKV_EINVAL on any violation.
  */
 int maskkv_bench_probe(int which, int32_t iters, const void* src, void* dst, int64_t bytes, int64_t dst_bytes,
                        int32_t groups, void* stream, double* work);

@@ -31,7 +31,9 @@ _lib = _load()
 def maskkv_bench_probe(which: int, iters: int, src: Optional[torch.Tensor], dst: torch.Tensor, groups: int,
                        stream=None) -> float:
     """Enqueue a probe (0 matrix pipe on constants, 1 v_exp_f32, 2 copy src -> dst, 3 read of src, 4 the scoring
-    instruction mix, 5 matrix pipe on the data in src, 6 the form-and-reduce pipeline on the data in src); returns the work it does (flops, exponentials or bytes)."""
+    instruction mix, 5 matrix pipe on the data in src, 6 the form-and-reduce pipeline on the data in src, 7 / 8 / 9 eight-
+    wave workgroups whose waves 0-3 issue MFMAs on the data in src and whose waves 4-7 issue the vector work: both
+    halves, the matrix half alone, the vector half alone); returns the work it does (flops, exponentials or bytes)."""
     work = ct.c_double(0.0)
     nbytes = src.numel() * src.element_size() if src is not None else 0
     status = _lib.maskkv_bench_probe(ct.c_int(which), ct.c_int32(iters), _b._ptr(src) if src is not None else None,

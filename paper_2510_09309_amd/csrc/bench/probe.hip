@@ -145,6 +145,59 @@ __global__ __launch_bounds__(kProbeThreads) void probe_pipeline_kernel(int iters
   out[(int64_t)blockIdx.x * kProbeThreads + threadIdx.x] = s;
 }
 
+// Do the matrix pipe and the vector pipe of a SIMD work at the same time for different waves?  Workgroups of eight
+// waves (waves w and w + 4 share a SIMD): per iteration waves 0-3 issue the sixteen MFMAs of probe_mfma_data_kernel,
+// waves 4-7 the 32 x (multiply, v_exp_f32, add) of a logits block pair.  WHO = 0: both halves work, 1: the matrix
+// half alone (the other half exits at once), 2: the vector half alone.
+constexpr int kSplitThreads = 512;
+
+template <int WHO>
+__global__ __launch_bounds__(kSplitThreads) void probe_split_kernel(int iters, const u32x4* src, float* out) {
+  const int lane = threadIdx.x & 63;
+  const bool vector_half = threadIdx.x >= kSplitThreads / 2;
+  float s = 0.f;
+  if (!vector_half) {
+    if (WHO == 2) return;
+    u32x4 ka[8], qf[8];  // (sixteen operand sets: a 512-thread workgroup leaves a wave 128 registers)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      ka[i] = src[lane + 64 * i];
+      qf[i] = src[lane + 64 * (16 + i)];
+    }
+    f32x16 acc[2] = {f32x16{}, f32x16{}};
+    for (int it = 0; it < iters; it += 2) {
+      qf[0][0] ^= 0x00010000u;  // the lowest mantissa bit of one bf16 operand element
+#pragma unroll
+      for (int half = 0; half < 2; ++half)
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+          for (int blk = 0; blk < 2; ++blk) mfma_step<bf16_t>(ka[(ks + blk + half) & 7], qf[ks], acc[blk]);
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s += acc[u][i];
+  } else {
+    if (WHO == 1) return;
+    float x[32], sum[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < 32; ++u) x[u] = 0.01f * (float)(lane + u + 1);
+    const float c = 0.127f;
+    for (int it = 0; it < iters; it += 2) {
+#pragma unroll
+      for (int half = 0; half < 2; ++half)
+#pragma unroll
+        for (int u = 0; u < 32; ++u) {
+          x[u] = fast_exp2(x[u] * c);
+          sum[u & 3] += x[u];
+        }
+    }
+    s = (sum[0] + sum[1]) + (sum[2] + sum[3]);
+  }
+  out[(int64_t)blockIdx.x * kSplitThreads + threadIdx.x] = s;
+}
+
 // Every lane runs iters * kExpChains v_exp_f32 (x <- 2^-|x|: the sign and magnitude modifiers are free, the
 // values stay in (0, 1]).
 __global__ __launch_bounds__(kProbeThreads) void probe_exp_kernel(int iters, float* out) {
@@ -221,10 +274,10 @@ const char* maskkv_bench_last_error(void) { return g_bench_err; }
 int maskkv_bench_probe(int which, int32_t iters, const void* src, void* dst, int64_t bytes, int64_t dst_bytes,
                        int32_t groups, void* stream_, double* work) {
   hipStream_t stream = reinterpret_cast<hipStream_t>(stream_);
-  if (which < 0 || which > 6 || !dst || groups < 1 || groups > (1 << 20))
-    return fail("probe: which outside 0..6, dst NULL or groups outside 1..2^20");
-  if (which != 2 && dst_bytes < (int64_t)groups * kProbeThreads * 4)
-    return fail("probe: dst is smaller than groups*256 words");
+  if (which < 0 || which > 9 || !dst || groups < 1 || groups > (1 << 20))
+    return fail("probe: which outside 0..9, dst NULL or groups outside 1..2^20");
+  if (which != 2 && dst_bytes < (int64_t)groups * (which >= 7 ? kSplitThreads : kProbeThreads) * 4)
+    return fail("probe: dst is smaller than one word per launched thread");
   const bool arithmetic = which == 0 || which == 1 || which >= 4;
   if (arithmetic && iters < 1) return fail("probe: iters < 1");
   if (which >= 5 && (!src || ((uintptr_t)src & 15) || bytes < 64 * 24 * 16))
@@ -241,6 +294,9 @@ int maskkv_bench_probe(int which, int32_t iters, const void* src, void* dst, int
       case 2: *work = 2.0 * (double)bytes; break;
       case 3: *work = (double)bytes; break;
       case 6: *work = waves * 16.0 * ((iters + 1) / 2 * 2) * 32768.0; break;  // (iterations come in pairs)
+      case 7:  // (iterations come in pairs)
+      case 8: *work = (double)groups * 4 * 16.0 * ((iters + 1) / 2 * 2) * 32768.0; break;  // four matrix waves per workgroup
+      case 9: *work = (double)groups * 256 * 32.0 * ((iters + 1) / 2 * 2); break;  // exponentials of the vector half
       default: *work = waves * 16.0 * iters * 32768.0; break;  // 4, 5: sixteen MFMAs per iteration
     }
   }
@@ -267,6 +323,18 @@ int maskkv_bench_probe(int which, int32_t iters, const void* src, void* dst, int
       hipLaunchKernelGGL(probe_mfma_data_kernel, dim3(groups), dim3(kProbeThreads), 0, stream, iters,
                          reinterpret_cast<const u32x4*>(src), out);
       return launched("probe (mfma on data)");
+    case 7:
+      hipLaunchKernelGGL(probe_split_kernel<0>, dim3(groups), dim3(kSplitThreads), 0, stream, iters,
+                         reinterpret_cast<const u32x4*>(src), out);
+      return launched("probe (matrix waves and vector waves)");
+    case 8:
+      hipLaunchKernelGGL(probe_split_kernel<1>, dim3(groups), dim3(kSplitThreads), 0, stream, iters,
+                         reinterpret_cast<const u32x4*>(src), out);
+      return launched("probe (matrix waves alone)");
+    case 9:
+      hipLaunchKernelGGL(probe_split_kernel<2>, dim3(groups), dim3(kSplitThreads), 0, stream, iters,
+                         reinterpret_cast<const u32x4*>(src), out);
+      return launched("probe (vector waves alone)");
     default:
       hipLaunchKernelGGL(probe_pipeline_kernel, dim3(groups), dim3(kProbeThreads), 0, stream, iters,
                          reinterpret_cast<const u32x4*>(src), out);

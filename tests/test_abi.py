@@ -51,7 +51,9 @@ def test_bench_library_exports_its_header_and_rejects_bad_probes():
     probe = lambda which, iters, src, nbytes, dst_bytes, groups: lib.maskkv_bench_probe(
         ct.c_int(which), ct.c_int32(iters), src, f, ct.c_int64(nbytes), ct.c_int64(dst_bytes), ct.c_int32(groups), None,
         None)
-    assert probe(7, 10, None, 0, 1 << 20, 8) == 1              # unknown probe
+    assert probe(10, 10, None, 0, 1 << 20, 8) == 1             # unknown probe
+    assert probe(7, 10, None, 0, 1 << 20, 8) == 1              # split-role probe: operands missing
+    assert probe(7, 10, f, 64 * 24 * 16, 8 * 512 * 4 - 4, 8) == 1   # split-role probe: one word per thread of 512
     assert probe(6, 10, None, 0, 1 << 20, 8) == 1              # pipeline probe: operands missing
     assert probe(4, 0, None, 0, 1 << 20, 8) == 1               # no iterations
     assert probe(0, 0, None, 0, 1 << 20, 8) == 1               # no iterations

@@ -85,6 +85,9 @@ def test_measurement_probes_run_and_the_copy_is_exact():
     out.fill_(float("nan"))
     assert bb.maskkv_bench_probe(5, 10, operands, out, 8) == 8 * 4 * 16 * 10 * 32768.0
     assert bb.maskkv_bench_probe(6, 9, operands, out, 8) == 8 * 4 * 16 * 10 * 32768.0      # iterations run in pairs
+    assert bb.maskkv_bench_probe(7, 10, operands, out, 4) == 4 * 4 * 16 * 10 * 32768.0     # matrix and vector halves
+    assert bb.maskkv_bench_probe(8, 10, operands, out, 4) == 4 * 4 * 16 * 10 * 32768.0     # the matrix half alone
+    assert bb.maskkv_bench_probe(9, 10, operands, out, 4) == 4 * 256 * 32 * 10             # the vector half alone
     torch.cuda.synchronize()
     assert bool(torch.isfinite(out).all())
     src = torch.arange(100003 * 4, dtype=torch.int32, device="cuda")               # a ragged number of 16-byte pieces
