@@ -129,6 +129,7 @@ __global__ __launch_bounds__((ScoreCfg<T, D, PASS>::kThreads), (ScoreCfg<T, D, P
   const int r = lane & 31;
   const int g = lane >> 5;
   const float c = prm.c;
+  const float inv_c = 1.0f / c;
   const TileMap& map = prm.map;
 
   int s = map.first_tile(blockIdx.x);
@@ -165,7 +166,20 @@ __global__ __launch_bounds__((ScoreCfg<T, D, PASS>::kThreads), (ScoreCfg<T, D, P
 
     {
       const int q0 = qg + wave * C::kQPerWave;
-      if (bh != cur_bh || qg != cur_qg) {
+      const bool new_head = bh != cur_bh || qg != cur_qg;
+      // Loads return in the order of their issue.  (Pass 2, on entering a head) this thread's row normaliser is asked
+      // for first - the first barrier below waits for it and for nothing else - then the segment's first K tile,
+      // then the query fragments, which are not needed before the first MFMA.
+      float my_nlse = 0.f;
+      if (PASS == 2 && new_head && (int)threadIdx.x < kQPerGroup) {
+        const int q = qg + (int)threadIdx.x;
+        my_nlse = q >= prm.n_query ? -INFINITY
+                  : prm.row_lse    ? -prm.row_lse[(int64_t)bh * prm.n_query + q] * kLog2e
+                                   : -prm.lse2[(int64_t)bh * prm.n_query + q];
+      }
+      u32x4 stage[C::kPieces];
+      load_tile_global<T, D, PASS>(kbase, kstride, k0, k1 - 1, stage);
+      if (new_head) {
         cur_bh = bh;
         cur_qg = qg;
         // Query fragments stay in registers for as long as the walk stays in this head.  Rows past
@@ -181,16 +195,14 @@ __global__ __launch_bounds__((ScoreCfg<T, D, PASS>::kThreads), (ScoreCfg<T, D, P
         }
         if (PASS == 2) {
           __syncthreads();
-          const int q = qg + (int)threadIdx.x;
-          if ((int)threadIdx.x < kQPerGroup)
-            nlse[threadIdx.x] = q >= prm.n_query ? -INFINITY
-                                : prm.row_lse    ? -prm.row_lse[(int64_t)bh * prm.n_query + q] * kLog2e
-                                                 : -prm.lse2[(int64_t)bh * prm.n_query + q];
+          if ((int)threadIdx.x < kQPerGroup) nlse[threadIdx.x] = my_nlse;
           __syncthreads();
+          // (one reciprocal instead of 32 divisions, each a chain of about ten dependent instructions; the start
+          // value moves by one ulp at most, a probability by 1e-6 relative)
 #pragma unroll
           for (int blk = 0; blk < C::kNQ; ++blk)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) nb[blk][i] = nlse[wave * C::kQPerWave + blk * 32 + 8 * (i / 4) + 4 * g + (i % 4)] / c;
+            for (int i = 0; i < 16; ++i) nb[blk][i] = nlse[wave * C::kQPerWave + blk * 32 + 8 * (i / 4) + 4 * g + (i % 4)] * inv_c;
         }
       }
 
@@ -290,10 +302,8 @@ __global__ __launch_bounds__((ScoreCfg<T, D, PASS>::kThreads), (ScoreCfg<T, D, P
       //   stage 1 of iteration t: form (t,1) -> B  |  reduce (t,0) from A
       //   tile t+1: registers -> LDS, barrier, request tile t+2 from global memory
       //   stage 2 of iteration t: form (t+1,0) -> A  |  reduce (t,1) from B
-      u32x4 stage[C::kPieces];
       f32x16 accA[C::kNQ], accB[C::kNQ];
       __syncthreads();  // the previous segment's readers are done with the tile and partial buffers
-      load_tile_global<T, D, PASS>(kbase, kstride, k0, k1 - 1, stage);
       store_tile_lds<T, D, PASS>(kt_raw, stage);
       if (nt > 1) load_tile_global<T, D, PASS>(kbase, kstride, k0 + C::kTK, k1 - 1, stage);
       __syncthreads();
