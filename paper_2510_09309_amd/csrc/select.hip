@@ -211,8 +211,9 @@ __device__ __forceinline__ uint32_t wave_max(uint32_t v) {
   return (uint32_t)__builtin_amdgcn_readlane(r, 63);
 }
 
-// ---- chunk stage: grid (BH, max_chunks)
-__global__ __launch_bounds__(kSelThreads) void select_chunk_kernel(const SelectParams prm) {
+// ---- chunk stage: grid (BH, max_chunks).  Eight waves per SIMD, i.e. at most 64 registers: two of these 1024-thread
+// workgroups then fit a compute unit, which halves the rounds a batch with more chunks than compute units needs.
+__global__ __launch_bounds__(kSelThreads, 8) void select_chunk_kernel(const SelectParams prm) {
   __shared__ int hist[kHistWords];
   __shared__ uint32_t wmin[kSelWaves], wmax[kSelWaves];
   __shared__ int wsum[kSelWaves];
