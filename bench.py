@@ -39,7 +39,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
 # HBM bytes read + written by one launch of score pass 1 at the 32k prompt: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE,
 # each scaled by what it reads for a copy of known size (profiles/score_pass1_c4_hbm_traffic.md).  Other workloads: null.
-SCORE_PASS1_TRAFFIC_BYTES = {"C4": 141370.7 * 1024 * 2.0 + 1126.0 * 1024}
+SCORE_PASS1_TRAFFIC_BYTES = {"C4": 141373.0 * 1024 * 2.0 + 1126.0 * 1024}
 
 
 def workload(name: str) -> dict:
